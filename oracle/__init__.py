@@ -1,0 +1,125 @@
+"""CPU oracle for the sparse ternary GEMM Y = X W + b -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around oracle/tstgemm_oracle.c (see that file for what it follows in the
+paper).  Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package; the product package never does.  It imports nothing from the product package.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(str(path))
+        lib.oracle_tstgemm_rows.restype = ctypes.c_int
+        lib.oracle_tstgemm_points.restype = ctypes.c_int
+        lib.oracle_tcsc_build.restype = ctypes.c_int
+        lib.oracle_tcsc_count.restype = ctypes.c_int
+        lib.oracle_tcsc_to_dense.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+@dataclass
+class Tcsc:
+    """The four TCSC arrays of Sec. 2 (int32, 0-based) plus the shape of W."""
+    col_start_pos: np.ndarray
+    col_start_neg: np.ndarray
+    row_index_pos: np.ndarray
+    row_index_neg: np.ndarray
+    K: int
+    N: int
+
+    @property
+    def nnz(self) -> int:
+        return int(self.row_index_pos.size + self.row_index_neg.size)
+
+    def negated(self) -> "Tcsc":
+        """TCSC of -W: the two sign lists trade places."""
+        return Tcsc(self.col_start_neg, self.col_start_pos, self.row_index_neg, self.row_index_pos, self.K, self.N)
+
+
+def tcsc_build(W: np.ndarray) -> Tcsc:
+    W = np.ascontiguousarray(W, dtype=np.int8)
+    K, N = W.shape
+    lib = _load()
+    p, q = ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = lib.oracle_tcsc_count(_p(W), K, N, ctypes.byref(p), ctypes.byref(q))
+    if rc:
+        raise ValueError(f"oracle_tcsc_count failed ({rc}): W must hold only -1, 0, +1")
+    csp = np.empty(N + 1, np.int32)
+    csn = np.empty(N + 1, np.int32)
+    rip = np.empty(p.value, np.int32)
+    rin = np.empty(q.value, np.int32)
+    rc = lib.oracle_tcsc_build(_p(W), K, N, _p(csp), _p(csn), _p(rip), _p(rin))
+    if rc:
+        raise ValueError(f"oracle_tcsc_build failed ({rc})")
+    return Tcsc(csp, csn, rip, rin, K, N)
+
+
+def tcsc_to_dense(t: Tcsc) -> np.ndarray:
+    W = np.empty((t.K, t.N), np.int8)
+    rc = _load().oracle_tcsc_to_dense(_p(t.col_start_pos), _p(t.col_start_neg), _p(t.row_index_pos),
+                                      _p(t.row_index_neg), t.K, t.N, _p(W))
+    if rc:
+        raise ValueError(f"oracle_tcsc_to_dense failed ({rc})")
+    return W
+
+
+def tstgemm(X: np.ndarray, t: Tcsc, b: np.ndarray | None, rows=None, threads: int = 0):
+    """(Yd, A, threads_used): all rows of Y, or the rows listed in `rows`, in float64."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    M, K = X.shape
+    if K != t.K:
+        raise ValueError("X has the wrong number of columns")
+    if b is not None:
+        b = np.ascontiguousarray(b, dtype=np.float32)
+        if b.shape != (t.N,):
+            raise ValueError("b has the wrong length")
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        if rows.size and (rows.min() < 0 or rows.max() >= M):
+            raise ValueError("row out of range")
+    n_rows = M if rows is None else int(rows.size)
+    Yd = np.empty((n_rows, t.N), np.float64)
+    A = np.empty((n_rows, t.N), np.float64)
+    used = _load().oracle_tstgemm_rows(_p(X), _p(t.col_start_pos), _p(t.col_start_neg), _p(t.row_index_pos),
+                                       _p(t.row_index_neg), _p(b), _p(rows), n_rows, M, K, t.N, _p(Yd), _p(A),
+                                       int(threads))
+    if used < 0:
+        raise ValueError(f"oracle_tstgemm_rows failed ({used})")
+    return Yd, A, used
+
+
+def tstgemm_points(X: np.ndarray, t: Tcsc, b: np.ndarray | None, ms, ns):
+    """(Yd, A) for the sampled elements (ms[i], ns[i])."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    M, K = X.shape
+    if K != t.K:
+        raise ValueError("X has the wrong number of columns")
+    if b is not None:
+        b = np.ascontiguousarray(b, dtype=np.float32)
+    ms = np.ascontiguousarray(ms, dtype=np.int32)
+    ns = np.ascontiguousarray(ns, dtype=np.int32)
+    Yd = np.empty(ms.size, np.float64)
+    A = np.empty(ms.size, np.float64)
+    rc = _load().oracle_tstgemm_points(_p(X), _p(t.col_start_pos), _p(t.col_start_neg), _p(t.row_index_pos),
+                                       _p(t.row_index_neg), _p(b), _p(ms), _p(ns), ctypes.c_int64(ms.size),
+                                       M, K, t.N, _p(Yd), _p(A))
+    if rc:
+        raise ValueError(f"oracle_tstgemm_points failed ({rc})")
+    return Yd, A
