@@ -1,0 +1,131 @@
+/*
+ * tstgemm -- sparse ternary GEMM  Y = X W + b  for one AMD MI355X (gfx950).
+ *
+ * C ABI of libtstgemm.so.  Plain pointers and sizes only; every pointer argument says
+ * whether it is HOST or DEVICE memory.  All functions return 0 (TSTGEMM_OK) or a negative
+ * TSTGEMM_E* code; tcsc_strerror() turns a code into text.  No function throws, aborts or
+ * prints.  The library keeps no global state besides what a handle owns.
+ *
+ * The operation is Eq. 1 of the paper (Sec. 2): X is dense fp32 (M x K, row-major), W is a
+ * K x N matrix with entries in {-1, 0, +1}, b (N) is added to every row of the product,
+ * Y is fp32 (M x N, row-major).  W is held in the TCSC format of Sec. 2: four int32 arrays,
+ * col_start_pos / col_start_neg (N+1 column pointers) and row_index_pos / row_index_neg
+ * (row numbers of the +1 / -1 entries, column after column, ascending inside a column; the
+ * entries of column j are [col_start[j], col_start[j+1])).  The product is evaluated with
+ * additions and subtractions only (BaseTCSC, Sec. 2): X entries whose weight is 0 are never
+ * read, so a non-finite value there does not reach Y.
+ */
+#ifndef TSTGEMM_H
+#define TSTGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TSTGEMM_OK 0
+#define TSTGEMM_EINVAL (-1)       /* null pointer, non-positive dimension, K/N differ from the handle's */
+#define TSTGEMM_EFORMAT (-2)      /* W entry outside {-1,0,1}; pointers not monotone; row out of [0,K);
+                                     rows of a column not strictly ascending; a row in both lists of a column */
+#define TSTGEMM_ENOTUPLOADED (-3) /* tstgemm() on a handle that tcsc_upload() has not filled */
+#define TSTGEMM_EHIP (-4)         /* a HIP runtime call failed (launch, copy) */
+#define TSTGEMM_ENOMEM (-5)       /* host allocation failed, or the device buffer passed in is too small */
+#define TSTGEMM_ETOOBIG (-6)      /* more than 2^31-1 entries in one sign list, or K >= 2^31 */
+
+/* Opaque handle: owns a host copy of the four TCSC arrays; after tcsc_upload() it also
+ * remembers (borrows, never frees) the caller's device buffer holding the device form. */
+typedef struct tcsc tcsc_t;
+
+/*
+ * TCSC construction (Sec. 2, the four arrays), on the host.
+ * W: HOST, K*N int8, row-major (W[k*N + n]), every value in {-1, 0, +1}.
+ * *out receives a new handle (release with tcsc_destroy).  K, N >= 1.
+ * Errors: EINVAL, EFORMAT (bad value), ETOOBIG, ENOMEM.
+ */
+int tcsc_build(const int8_t *W, int K, int N, tcsc_t **out);
+
+/*
+ * Handle from existing TCSC arrays (Sec. 2).  All four arrays HOST; they are validated
+ * (see EFORMAT) and copied, the caller keeps ownership of its own.
+ * col_start_*: N+1 entries, col_start[0] == 0; row_index_*: col_start_*[N] entries, 0-based.
+ */
+int tcsc_from_arrays(const int32_t *col_start_pos, const int32_t *col_start_neg,
+                     const int32_t *row_index_pos, const int32_t *row_index_neg,
+                     int K, int N, tcsc_t **out);
+
+/* Dense form of the handle's matrix: W_out HOST, K*N int8 row-major, fully overwritten. */
+int tcsc_to_dense(const tcsc_t *t, int8_t *W_out);
+
+/* Shape and the number of +1 / -1 entries.  Any output pointer may be NULL. */
+int tcsc_dims(const tcsc_t *t, int *K, int *N, int64_t *nnz_pos, int64_t *nnz_neg);
+
+/* Borrow the handle's HOST copies of the four arrays (valid until tcsc_destroy). */
+int tcsc_arrays(const tcsc_t *t, const int32_t **col_start_pos, const int32_t **col_start_neg,
+                const int32_t **row_index_pos, const int32_t **row_index_neg);
+
+/* Bytes of DEVICE memory tcsc_upload() needs for this matrix (256-byte aligned sections). */
+int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
+
+/*
+ * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
+ * the four TCSC arrays unchanged (read by the small-M kernel) and their K-blocked form
+ * (read by the large-M kernel).  K-blocking follows the idea of BlockedTCSC (Sec. 3,
+ * "Blocking"): the rows [0,K) are cut into blocks of k_block rows so that all X entries one
+ * block touches fit in the LDS, and every column's lists are cut at the block borders.
+ *
+ *   seg_count  int32 [n_kblocks][n_pad]   low 16 bits: number of +1 rows of column n inside
+ *                                         K-block kb, high 16 bits: number of -1 rows
+ *   col_ptr    int64 [n_pad + 1]          start of column n's stream, in int32 units
+ *   stream     int32 [stream_len]         for column n, K-block after K-block: the +1 rows of
+ *                                         the block as block-local row numbers (row - kb*k_block),
+ *                                         then the -1 rows, each list stored in chunks of
+ *                                         `chunk` slots.  Full chunks come first.  A last partial
+ *                                         chunk with r entries (binary r = 4a+2b+c) keeps 4a
+ *                                         entries in slots 0..3, 2b in slots 4..5, c in slot 6;
+ *                                         unused slots hold 0 and are never read by the kernel.
+ * n_pad = N rounded up to a multiple of 64; columns >= N have empty lists.
+ */
+typedef struct tcsc_layout {
+    int32_t K, N, n_pad, k_block, n_kblocks, chunk;
+    int64_t nnz_pos, nnz_neg, stream_len;
+    size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
+    size_t off_seg_count, off_col_ptr, off_stream, total_bytes;
+} tcsc_layout_t;
+
+int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);
+
+/*
+ * Copy the four arrays to the device and run the GPU re-blocking pass into dev_buf.
+ * dev_buf: DEVICE, at least tcsc_device_bytes() bytes, 256-byte aligned, owned by the
+ * caller; the handle keeps the pointer until tcsc_destroy() and never frees it.  The buffer
+ * must stay untouched while the handle is in use.  stream: a hipStream_t (NULL = the null
+ * stream).  Work is enqueued on `stream`; the host arrays are read before the call returns.
+ * Errors: EINVAL, ENOMEM (bytes too small), EHIP.
+ */
+int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
+
+/*
+ * Y = X W + b  (Eq. 1; evaluation as BaseTCSC, Sec. 2: gather-add the +1 rows, gather-subtract
+ * the -1 rows, bias added once at the end).
+ * X: DEVICE fp32 M*K row-major.  b: DEVICE fp32 N, or NULL for b = 0.  Y: DEVICE fp32 M*N
+ * row-major, fully overwritten; must not overlap X, b or the handle's device buffer.
+ * M >= 1 arbitrary; K, N must equal the handle's.  Asynchronous: the kernels are enqueued on
+ * `stream` (a hipStream_t, NULL = null stream), no host synchronisation, no allocation.
+ * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, EHIP (launch failure).
+ * Rounding: fp32 accumulation in an order fixed by (M, K, N) and the matrix; repeated calls
+ * give bit-identical results.  Integer-valued inputs small enough for fp32 give exact results.
+ */
+int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
+
+/* Release the handle and its host arrays (not the device buffer).  NULL is allowed. */
+void tcsc_destroy(tcsc_t *t);
+
+/* Static text for a return code. */
+const char *tcsc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSTGEMM_H */

@@ -1,0 +1,216 @@
+"""ctypes binding of libtstgemm.so -- same names as the C entry points in include/tstgemm.h.
+
+Nothing is computed here.  If the shared library has not been built the first call raises:
+there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import pathlib
+
+import numpy as np
+
+_HERE = pathlib.Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libtstgemm.so"
+_lib = None
+
+
+class TstgemmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {tcsc_strerror(code)} (code {code})")
+
+
+class TcscLayout(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("n_pad", ctypes.c_int32), ("k_block", ctypes.c_int32),
+                ("n_kblocks", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("nnz_pos", ctypes.c_int64), ("nnz_neg", ctypes.c_int64), ("stream_len", ctypes.c_int64),
+                ("off_col_start_pos", ctypes.c_size_t), ("off_col_start_neg", ctypes.c_size_t),
+                ("off_row_index_pos", ctypes.c_size_t), ("off_row_index_neg", ctypes.c_size_t),
+                ("off_seg_count", ctypes.c_size_t), ("off_col_ptr", ctypes.c_size_t), ("off_stream", ctypes.c_size_t),
+                ("total_bytes", ctypes.c_size_t)]
+
+
+def library_path() -> pathlib.Path:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_06957_amd.build` "
+                           "(there is no fallback implementation)")
+    # PyTorch ships its own copy of the HIP runtime.  Device pointers and streams are only valid inside the
+    # runtime that created them, so torch must be in the process first: the loader then resolves this library's
+    # libamdhip64 dependency to the copy torch already mapped instead of opening a second runtime.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(str(_LIB_PATH))
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.tcsc_build.argtypes = [vp, ci, ci, ctypes.POINTER(vp)]
+    lib.tcsc_from_arrays.argtypes = [vp, vp, vp, vp, ci, ci, ctypes.POINTER(vp)]
+    lib.tcsc_to_dense.argtypes = [vp, vp]
+    lib.tcsc_dims.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_int64),
+                              ctypes.POINTER(ctypes.c_int64)]
+    lib.tcsc_arrays.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.tcsc_device_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.tcsc_layout.argtypes = [vp, ctypes.POINTER(TcscLayout)]
+    lib.tcsc_upload.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.tstgemm.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.tcsc_destroy.argtypes = [vp]
+    lib.tcsc_destroy.restype = None
+    lib.tcsc_strerror.argtypes = [ci]
+    lib.tcsc_strerror.restype = ctypes.c_char_p
+    for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
+                 "tcsc_layout", "tcsc_upload", "tstgemm"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def tcsc_strerror(code: int) -> str:
+    return _load().tcsc_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise TstgemmError(code, where)
+
+
+def _np_ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+class Tcsc:
+    """Owner of a tcsc_t handle (and, once uploaded, of the torch tensor backing its device form)."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+        self.device_buffer = None
+        self.K, self.N, self.nnz_pos, self.nnz_neg = tcsc_dims(self)
+
+    @property
+    def nnz(self) -> int:
+        return self.nnz_pos + self.nnz_neg
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("tcsc handle already destroyed")
+        return self._h
+
+    def __del__(self):
+        try:
+            tcsc_destroy(self)
+        except Exception:
+            pass
+
+
+def tcsc_build(W: np.ndarray) -> Tcsc:
+    """TCSC handle from a dense ternary matrix (host, K x N, values in {-1,0,+1})."""
+    W = np.ascontiguousarray(W, dtype=np.int8)
+    if W.ndim != 2:
+        raise ValueError("W must be a K x N matrix")
+    out = ctypes.c_void_p()
+    _check(_load().tcsc_build(_np_ptr(W), W.shape[0], W.shape[1], ctypes.byref(out)), "tcsc_build")
+    return Tcsc(out.value)
+
+
+def tcsc_from_arrays(col_start_pos, col_start_neg, row_index_pos, row_index_neg, K: int, N: int) -> Tcsc:
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (col_start_pos, col_start_neg, row_index_pos,
+                                                               row_index_neg)]
+    if arrs[0].size != N + 1 or arrs[1].size != N + 1:
+        raise ValueError("col_start arrays need N + 1 entries")
+    if arrs[0].size and (arrs[2].size < arrs[0][-1] or arrs[3].size < arrs[1][-1]):
+        raise ValueError("row_index arrays shorter than col_start[N]")
+    out = ctypes.c_void_p()
+    _check(_load().tcsc_from_arrays(*[_np_ptr(a) for a in arrs], int(K), int(N), ctypes.byref(out)),
+           "tcsc_from_arrays")
+    return Tcsc(out.value)
+
+
+def tcsc_to_dense(t: Tcsc) -> np.ndarray:
+    W = np.empty((t.K, t.N), np.int8)
+    _check(_load().tcsc_to_dense(t.handle, _np_ptr(W)), "tcsc_to_dense")
+    return W
+
+
+def tcsc_dims(t: Tcsc):
+    K, N = ctypes.c_int(), ctypes.c_int()
+    p, q = ctypes.c_int64(), ctypes.c_int64()
+    _check(_load().tcsc_dims(t.handle, ctypes.byref(K), ctypes.byref(N), ctypes.byref(p), ctypes.byref(q)),
+           "tcsc_dims")
+    return K.value, N.value, p.value, q.value
+
+
+def tcsc_arrays(t: Tcsc):
+    """Copies of the handle's four host arrays (col_start_pos, col_start_neg, row_index_pos, row_index_neg)."""
+    ptrs = [ctypes.c_void_p() for _ in range(4)]
+    _check(_load().tcsc_arrays(t.handle, *[ctypes.byref(p) for p in ptrs]), "tcsc_arrays")
+    sizes = [t.N + 1, t.N + 1, t.nnz_pos, t.nnz_neg]
+    out = []
+    for p, n in zip(ptrs, sizes):
+        if n == 0:
+            out.append(np.empty(0, np.int32))
+        else:
+            out.append(np.ctypeslib.as_array(ctypes.cast(p, ctypes.POINTER(ctypes.c_int32)), shape=(n,)).copy())
+    return tuple(out)
+
+
+def tcsc_device_bytes(t: Tcsc) -> int:
+    n = ctypes.c_size_t()
+    _check(_load().tcsc_device_bytes(t.handle, ctypes.byref(n)), "tcsc_device_bytes")
+    return n.value
+
+
+def tcsc_layout(t: Tcsc) -> TcscLayout:
+    lay = TcscLayout()
+    _check(_load().tcsc_layout(t.handle, ctypes.byref(lay)), "tcsc_layout")
+    return lay
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
+    """Allocate the device buffer with torch and run the upload + GPU re-blocking pass into it."""
+    import torch
+    dev = torch.device(device)
+    with torch.cuda.device(dev):
+        buf = torch.empty(tcsc_device_bytes(t) + 256, dtype=torch.uint8, device=dev)
+        base = (buf.data_ptr() + 255) // 256 * 256
+        _check(_load().tcsc_upload(t.handle, ctypes.c_void_p(base), tcsc_device_bytes(t), _stream_ptr(stream)),
+               "tcsc_upload")
+    t.device_buffer = buf
+    t.device_base = base
+    return t
+
+
+def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None):
+    """Y = X W + b on the GPU.  X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None."""
+    import torch
+    if not (X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.dim() == 2):
+        raise ValueError("X must be a contiguous float32 CUDA matrix")
+    M, K = X.shape
+    if b is not None and not (b.is_cuda and b.dtype == torch.float32 and b.is_contiguous() and b.numel() == t.N):
+        raise ValueError("b must be a contiguous float32 CUDA vector of length N")
+    if Y is None:
+        Y = torch.empty((M, t.N), dtype=torch.float32, device=X.device)
+    elif not (Y.is_cuda and Y.dtype == torch.float32 and Y.is_contiguous() and tuple(Y.shape) == (M, t.N)):
+        raise ValueError("Y must be a contiguous float32 CUDA matrix of shape [M, N]")
+    with torch.cuda.device(X.device):
+        _check(_load().tstgemm(ctypes.c_void_p(X.data_ptr()), t.handle,
+                               None if b is None else ctypes.c_void_p(b.data_ptr()), ctypes.c_void_p(Y.data_ptr()),
+                               int(M), int(K), int(t.N), _stream_ptr(stream)), "tstgemm")
+    return Y
+
+
+def tcsc_destroy(t: Tcsc):
+    if getattr(t, "_h", None) is not None:
+        _load().tcsc_destroy(t._h)
+        t._h = None
+        t.device_buffer = None

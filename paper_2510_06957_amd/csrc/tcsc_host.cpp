@@ -1,0 +1,259 @@
+// Host side of libtstgemm: handle, TCSC construction and validation (Sec. 2 of the paper),
+// device-buffer layout, upload and the tstgemm() dispatch.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "tstgemm_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Padded stream length of one column: every (K-block, sign) list rounded up to whole chunks.
+int64_t column_stream_len(const int32_t *rows_p, int np, const int32_t *rows_n, int nn, int n_kblocks)
+{
+    int64_t len = 0;
+    int ip = 0, in = 0;
+    for (int kb = 0; kb < n_kblocks; ++kb) {
+        const int64_t hi = (int64_t)(kb + 1) * tst::kKBlock;
+        int cp = 0, cn = 0;
+        while (ip < np && rows_p[ip] < hi) { ++ip; ++cp; }
+        while (in < nn && rows_n[in] < hi) { ++in; ++cn; }
+        len += tst::pad_chunk(cp) + tst::pad_chunk(cn);
+    }
+    return len;
+}
+
+void compute_layout(tcsc *t)
+{
+    tcsc_layout_t &l = t->layout;
+    l.K = t->K;
+    l.N = t->N;
+    l.n_pad = (t->N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
+    l.k_block = tst::kKBlock;
+    l.n_kblocks = (t->K + tst::kKBlock - 1) / tst::kKBlock;
+    l.chunk = tst::kChunk;
+    l.nnz_pos = (int64_t)t->row_index_pos.size();
+    l.nnz_neg = (int64_t)t->row_index_neg.size();
+    int64_t len = 0;
+    for (int n = 0; n < t->N; ++n) {
+        const int32_t p0 = t->col_start_pos[n], p1 = t->col_start_pos[n + 1];
+        const int32_t q0 = t->col_start_neg[n], q1 = t->col_start_neg[n + 1];
+        len += column_stream_len(t->row_index_pos.data() + p0, p1 - p0, t->row_index_neg.data() + q0, q1 - q0,
+                                 l.n_kblocks);
+    }
+    l.stream_len = len;
+    size_t off = 0;
+    auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    l.off_col_start_pos = place(sizeof(int32_t) * (size_t)(t->N + 1));
+    l.off_col_start_neg = place(sizeof(int32_t) * (size_t)(t->N + 1));
+    // + 4 entries of slack: the small-M kernel reads the lists in aligned groups of four
+    l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + 4));
+    l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + 4));
+    l.off_seg_count = place(sizeof(int32_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
+    l.off_col_ptr = place(sizeof(int64_t) * (size_t)(l.n_pad + 1));
+    l.off_stream = place(sizeof(int32_t) * (size_t)(len + tst::kChunk));
+    l.total_bytes = off;
+}
+
+// The structural rules of the format: monotone pointers starting at 0, rows inside [0,K),
+// strictly ascending inside a column, no row in both lists of a column.
+int validate(const int32_t *csp, const int32_t *csn, const int32_t *rip, const int32_t *rin, int K, int N)
+{
+    if (csp[0] != 0 || csn[0] != 0) return TSTGEMM_EFORMAT;
+    for (int n = 0; n < N; ++n)
+        if (csp[n + 1] < csp[n] || csn[n + 1] < csn[n]) return TSTGEMM_EFORMAT;
+    for (int n = 0; n < N; ++n) {
+        for (int32_t i = csp[n]; i < csp[n + 1]; ++i) {
+            if (rip[i] < 0 || rip[i] >= K) return TSTGEMM_EFORMAT;
+            if (i > csp[n] && rip[i] <= rip[i - 1]) return TSTGEMM_EFORMAT;
+        }
+        for (int32_t i = csn[n]; i < csn[n + 1]; ++i) {
+            if (rin[i] < 0 || rin[i] >= K) return TSTGEMM_EFORMAT;
+            if (i > csn[n] && rin[i] <= rin[i - 1]) return TSTGEMM_EFORMAT;
+        }
+        // both lists ascending: one merge pass finds a row present in both
+        int32_t i = csp[n], j = csn[n];
+        while (i < csp[n + 1] && j < csn[n + 1]) {
+            if (rip[i] == rin[j]) return TSTGEMM_EFORMAT;
+            if (rip[i] < rin[j]) ++i; else ++j;
+        }
+    }
+    return TSTGEMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tcsc_build(const int8_t *W, int K, int N, tcsc_t **out)
+{
+    if (!W || !out || K < 1 || N < 1) return TSTGEMM_EINVAL;
+    *out = nullptr;
+    try {
+        // pass 1: entries per column and sign (row-major scan, so W is read sequentially)
+        std::vector<int64_t> cnt_p((size_t)N + 1, 0), cnt_n((size_t)N + 1, 0);
+        for (int k = 0; k < K; ++k) {
+            const int8_t *row = W + (size_t)k * N;
+            for (int n = 0; n < N; ++n) {
+                const int8_t w = row[n];
+                if (w == 1) ++cnt_p[n + 1];
+                else if (w == -1) ++cnt_n[n + 1];
+                else if (w != 0) return TSTGEMM_EFORMAT;
+            }
+        }
+        for (int n = 0; n < N; ++n) { cnt_p[n + 1] += cnt_p[n]; cnt_n[n + 1] += cnt_n[n]; }
+        if (cnt_p[N] > INT32_MAX || cnt_n[N] > INT32_MAX) return TSTGEMM_ETOOBIG;
+        tcsc *t = new tcsc;
+        t->K = K;
+        t->N = N;
+        t->col_start_pos.assign(cnt_p.begin(), cnt_p.end());
+        t->col_start_neg.assign(cnt_n.begin(), cnt_n.end());
+        t->row_index_pos.resize((size_t)cnt_p[N]);
+        t->row_index_neg.resize((size_t)cnt_n[N]);
+        // pass 2: rows visited in ascending order, so every column's list comes out ascending
+        std::vector<int32_t> fill_p(t->col_start_pos.begin(), t->col_start_pos.end() - 1);
+        std::vector<int32_t> fill_n(t->col_start_neg.begin(), t->col_start_neg.end() - 1);
+        for (int k = 0; k < K; ++k) {
+            const int8_t *row = W + (size_t)k * N;
+            for (int n = 0; n < N; ++n) {
+                if (row[n] == 1) t->row_index_pos[(size_t)fill_p[n]++] = k;
+                else if (row[n] == -1) t->row_index_neg[(size_t)fill_n[n]++] = k;
+            }
+        }
+        compute_layout(t);
+        *out = t;
+        return TSTGEMM_OK;
+    } catch (const std::bad_alloc &) {
+        return TSTGEMM_ENOMEM;
+    }
+}
+
+int tcsc_from_arrays(const int32_t *csp, const int32_t *csn, const int32_t *rip, const int32_t *rin, int K, int N,
+                     tcsc_t **out)
+{
+    if (!csp || !csn || !out || K < 1 || N < 1) return TSTGEMM_EINVAL;
+    *out = nullptr;
+    if (csp[0] != 0 || csn[0] != 0) return TSTGEMM_EFORMAT;
+    for (int n = 0; n < N; ++n)
+        if (csp[n + 1] < csp[n] || csn[n + 1] < csn[n]) return TSTGEMM_EFORMAT;
+    if ((csp[N] > 0 && !rip) || (csn[N] > 0 && !rin)) return TSTGEMM_EINVAL;
+    if (int rc = validate(csp, csn, rip, rin, K, N)) return rc;
+    try {
+        tcsc *t = new tcsc;
+        t->K = K;
+        t->N = N;
+        t->col_start_pos.assign(csp, csp + N + 1);
+        t->col_start_neg.assign(csn, csn + N + 1);
+        t->row_index_pos.assign(rip, rip + csp[N]);
+        t->row_index_neg.assign(rin, rin + csn[N]);
+        compute_layout(t);
+        *out = t;
+        return TSTGEMM_OK;
+    } catch (const std::bad_alloc &) {
+        return TSTGEMM_ENOMEM;
+    }
+}
+
+int tcsc_to_dense(const tcsc_t *t, int8_t *W_out)
+{
+    if (!t || !W_out) return TSTGEMM_EINVAL;
+    std::memset(W_out, 0, (size_t)t->K * t->N);
+    for (int n = 0; n < t->N; ++n) {
+        for (int32_t i = t->col_start_pos[n]; i < t->col_start_pos[n + 1]; ++i)
+            W_out[(size_t)t->row_index_pos[i] * t->N + n] = 1;
+        for (int32_t i = t->col_start_neg[n]; i < t->col_start_neg[n + 1]; ++i)
+            W_out[(size_t)t->row_index_neg[i] * t->N + n] = -1;
+    }
+    return TSTGEMM_OK;
+}
+
+int tcsc_dims(const tcsc_t *t, int *K, int *N, int64_t *nnz_pos, int64_t *nnz_neg)
+{
+    if (!t) return TSTGEMM_EINVAL;
+    if (K) *K = t->K;
+    if (N) *N = t->N;
+    if (nnz_pos) *nnz_pos = (int64_t)t->row_index_pos.size();
+    if (nnz_neg) *nnz_neg = (int64_t)t->row_index_neg.size();
+    return TSTGEMM_OK;
+}
+
+int tcsc_arrays(const tcsc_t *t, const int32_t **csp, const int32_t **csn, const int32_t **rip, const int32_t **rin)
+{
+    if (!t) return TSTGEMM_EINVAL;
+    if (csp) *csp = t->col_start_pos.data();
+    if (csn) *csn = t->col_start_neg.data();
+    if (rip) *rip = t->row_index_pos.data();
+    if (rin) *rin = t->row_index_neg.data();
+    return TSTGEMM_OK;
+}
+
+int tcsc_device_bytes(const tcsc_t *t, size_t *bytes)
+{
+    if (!t || !bytes) return TSTGEMM_EINVAL;
+    *bytes = t->layout.total_bytes;
+    return TSTGEMM_OK;
+}
+
+int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out)
+{
+    if (!t || !out) return TSTGEMM_EINVAL;
+    *out = t->layout;
+    return TSTGEMM_OK;
+}
+
+int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
+{
+    if (!t || !dev_buf) return TSTGEMM_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign) return TSTGEMM_EINVAL;
+    if (bytes < t->layout.total_bytes) return TSTGEMM_ENOMEM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *d = static_cast<char *>(dev_buf);
+    const tcsc_layout_t &l = t->layout;
+    t->uploaded = false;
+    t->dev = dev_buf;
+    auto copy = [&](size_t off, const std::vector<int32_t> &v) {
+        if (v.empty()) return hipSuccess;
+        return hipMemcpyAsync(d + off, v.data(), v.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    };
+    if (copy(l.off_col_start_pos, t->col_start_pos) != hipSuccess) return TSTGEMM_EHIP;
+    if (copy(l.off_col_start_neg, t->col_start_neg) != hipSuccess) return TSTGEMM_EHIP;
+    if (copy(l.off_row_index_pos, t->row_index_pos) != hipSuccess) return TSTGEMM_EHIP;
+    if (copy(l.off_row_index_neg, t->row_index_neg) != hipSuccess) return TSTGEMM_EHIP;
+    // The sources are pageable host memory: wait until the copies have read them.
+    if (hipStreamSynchronize(s) != hipSuccess) return TSTGEMM_EHIP;
+    if (tst::launch_reblock(t, s) != hipSuccess) return TSTGEMM_EHIP;
+    t->uploaded = true;
+    return TSTGEMM_OK;
+}
+
+int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
+{
+    if (!X || !t || !Y || M < 1) return TSTGEMM_EINVAL;
+    if (K != t->K || N != t->N) return TSTGEMM_EINVAL;
+    if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, Y, M, s)
+                                               : tst::launch_large(X, t, b, Y, M, s);
+    return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
+}
+
+void tcsc_destroy(tcsc_t *t) { delete t; }
+
+const char *tcsc_strerror(int code)
+{
+    switch (code) {
+    case TSTGEMM_OK: return "ok";
+    case TSTGEMM_EINVAL: return "invalid argument (null pointer, non-positive size, or K/N differ from the handle)";
+    case TSTGEMM_EFORMAT: return "not a valid ternary matrix / TCSC structure";
+    case TSTGEMM_ENOTUPLOADED: return "handle has no device form: call tcsc_upload first";
+    case TSTGEMM_EHIP: return "a HIP runtime call failed";
+    case TSTGEMM_ENOMEM: return "out of host memory, or device buffer too small";
+    case TSTGEMM_ETOOBIG: return "matrix too large for 32-bit TCSC pointers";
+    default: return "unknown tstgemm error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,132 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the CPU oracle, element by
+element, on the same seeded inputs.  Integer work (re-blocked streams) is compared bit for bit,
+floating point within 1e-5 * (sum |X W| + |b|), integer-valued inputs bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_06957_amd as tg
+import synth_inputs as si
+from gpu_util import assert_close, assert_exact, decode_device_form, gpu_tstgemm
+
+pytestmark = pytest.mark.gpu
+
+# (M, K, N): tiny and odd shapes, sizes that span several tiles with ragged tails, both kernels
+SHAPES = [(1, 1, 1), (3, 37, 5), (2, 513, 65), (8, 64, 1), (5, 130, 9), (9, 37, 5), (17, 513, 65), (64, 512, 512),
+          (65, 200, 130), (100, 320, 70), (129, 130, 67), (200, 1000, 100), (257, 257, 65), (300, 64, 64)]
+
+
+@pytest.mark.parametrize("K,N,density", [(37, 5, 0.5), (513, 65, 0.5), (512, 512, 0.5), (1000, 130, 0.0625),
+                                         (64, 9, 1.0), (130, 70, 0.0)])
+def test_reblocked_streams_decode_to_w(K, N, density):
+    W, _, _ = si.make_inputs(1, K, N, density, "uniform", seed=200 + K + N)
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    Wdev, canon = decode_device_form(t)
+    assert np.array_equal(Wdev, W)
+    o = oracle.tcsc_build(W)
+    for a, e in zip(canon, (o.col_start_pos, o.col_start_neg, o.row_index_pos, o.row_index_neg)):
+        assert np.array_equal(a, e)
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+@pytest.mark.parametrize("dist", ["normal", "int8"])
+def test_small_shapes(M, K, N, dist):
+    W, X, b = si.make_inputs(M, K, N, 0.5, dist, seed=300 + M + K + N)
+    Y, _ = gpu_tstgemm(W, X, b)
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    if dist == "int8":
+        assert_exact(Y, Yd, f"{M}x{K}x{N} integer")
+    else:
+        assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+
+
+@pytest.mark.parametrize("M", [1, 4, 8, 40, 130, 256])
+def test_integer_x_real_bias_is_exact(M):
+    """The bias is added once, last: integer sums are exact, so one rounding decides the result."""
+    W, X, _ = si.make_inputs(M, 700, 96, 0.5, "int8", seed=17)
+    b = si.draw_dense(np.random.Generator(np.random.PCG64(18)), (96,), "normal")
+    Y, _ = gpu_tstgemm(W, X, b)
+    Yd, _, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    assert np.array_equal(Y, Yd.astype(np.float32))
+
+
+@pytest.mark.parametrize("M", [3, 70])
+def test_degenerate_matrices(M):
+    K, N = 150, 40
+    _, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=23)
+    # all zero: Y = b exactly; no bias: exact zeros
+    Y, h = gpu_tstgemm(np.zeros((K, N), np.int8), X, b)
+    assert np.array_equal(Y, np.broadcast_to(b, Y.shape))
+    Y0, _ = gpu_tstgemm(np.zeros((K, N), np.int8), X, None, handle=h)
+    assert np.all(Y0 == 0)
+    # all +1 / all -1 columns, one nonzero per column (a gather)
+    W = np.zeros((K, N), np.int8)
+    W[:, 0], W[:, 1] = 1, -1
+    pick = np.random.default_rng(1).integers(0, K, size=N - 2)
+    W[pick, np.arange(2, N)] = 1
+    Y, _ = gpu_tstgemm(W, X, None)
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), None)
+    assert_close(Y, Yd, A, "degenerate")
+    assert np.array_equal(Y[:, 2:], X[:, pick])
+
+
+def test_zero_weight_entries_of_x_are_never_read():
+    """Gather semantics (additions and subtractions only, Sec. 2): a non-finite X entry whose weights are all zero
+    must not reach Y -- also not through the padding of the index streams."""
+    for M in (4, 80):
+        W, X, b = si.make_inputs(M, 300, 50, 0.5, "normal", seed=29)
+        W[[0, 7, 64, 299], :] = 0
+        X[:, [0, 7, 64, 299]] = [np.nan, np.inf, -np.inf, np.nan]
+        Y, _ = gpu_tstgemm(W, X, b)
+        assert np.all(np.isfinite(Y))
+        Xf = X.copy()
+        Xf[:, [0, 7, 64, 299]] = 0
+        Yd, A, _ = oracle.tstgemm(Xf, oracle.tcsc_build(W), b)
+        assert_close(Y, Yd, A, f"nan-guard M={M}")
+
+
+def test_negation_and_repeatability():
+    W, X, b = si.make_inputs(96, 640, 128, 0.25, "normal", seed=31)
+    Y1, h = gpu_tstgemm(W, X, None)
+    Y2, _ = gpu_tstgemm(W, X, None, handle=h)
+    assert np.array_equal(Y1.view(np.uint32), Y2.view(np.uint32))   # same bits on every call
+    # -W swaps the two lists, which changes the fp32 summation order: equal within the tolerance, not bitwise
+    Yn, _ = gpu_tstgemm(-W, X, None)
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(-W), None)
+    assert_close(Yn, Yd, A, "negated W")
+    assert np.all(np.abs(Yn.astype(np.float64) + Y1) <= 2e-5 * A)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3a", "C3b", "C4-1", "C4-8"])
+@pytest.mark.parametrize("dist", [None, "int8"])
+def test_benchmark_configs_full(name, dist):
+    """Every element of the single-GPU benchmark configurations, in the launch configuration bench.py times."""
+    W, X, b = si.make_workload(name, dist=dist)
+    Y, _ = gpu_tstgemm(W, X, b)
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    if dist == "int8":
+        assert_exact(Y, Yd, f"{name} integer")
+    else:
+        assert_close(Y, Yd, A, name)
+
+
+@pytest.mark.parametrize("name", ["C5a", "C5c"])
+def test_prefill_config_sampled_rows(name):
+    """M=4096, K=N=8192: all of Y is computed on the GPU; the oracle checks 24 whole rows (one per M-tile and a few
+    more) plus 4096 scattered elements, and an integer-valued run is checked bit for bit on the same rows."""
+    w = si.WORKLOADS[name]
+    W, X, b = si.make_workload(name)
+    ot = oracle.tcsc_build(W)
+    Y, h = gpu_tstgemm(W, X, b)
+    rng = np.random.default_rng(77)
+    rows = np.unique(np.concatenate([np.arange(16) * 256 + rng.integers(0, 256, 16), [0, w.M - 1],
+                                     rng.integers(0, w.M, 6)])).astype(np.int32)
+    Yd, A, _ = oracle.tstgemm(X, ot, b, rows=rows)
+    assert_close(Y[rows], Yd, A, f"{name} rows")
+    ms, ns = rng.integers(0, w.M, 4096), rng.integers(0, w.N, 4096)
+    Yp, Ap = oracle.tstgemm_points(X, ot, b, ms, ns)
+    assert_close(Y[ms, ns], Yp, Ap, f"{name} points")
+    Xi = si.draw_dense(np.random.Generator(np.random.PCG64(5)), X.shape, "int8")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, b, rows=rows)
+    assert np.array_equal(Yi[rows], Ydi.astype(np.float32))
