@@ -70,28 +70,32 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
 
 /*
  * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
- * the four TCSC arrays unchanged (read by the small-M kernel) and their K-blocked form
- * (read by the large-M kernel).  K-blocking follows the idea of BlockedTCSC (Sec. 3,
- * "Blocking"): the rows [0,K) are cut into blocks of k_block rows so that all X entries one
- * block touches fit in the LDS, and every column's lists are cut at the block borders.
+ * the four TCSC arrays unchanged (read by the small-M kernel), their K-blocked form (read by
+ * the large-M kernel) and a workspace for split-K partial sums.  K-blocking follows the idea
+ * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block rows so
+ * that all X entries one block touches fit in the LDS, and every column's lists are cut at the
+ * block borders; as in the paper's blocked format the blocks are stored block after block.
  *
- *   seg_count  int32 [n_kblocks][n_pad]   low 16 bits: number of +1 rows of column n inside
+ *   seg_count  int32  [n_kblocks][n_pad]  low 16 bits: number of +1 rows of column n inside
  *                                         K-block kb, high 16 bits: number of -1 rows
- *   col_ptr    int64 [n_pad + 1]          start of column n's stream, in int32 units
- *   stream     int32 [stream_len]         for column n, K-block after K-block: the +1 rows of
- *                                         the block as block-local row numbers (row - kb*k_block),
- *                                         then the -1 rows, each list stored in chunks of
- *                                         `chunk` slots.  Full chunks come first.  A last partial
- *                                         chunk with r entries (binary r = 4a+2b+c) keeps 4a
- *                                         entries in slots 0..3, 2b in slots 4..5, c in slot 6;
- *                                         unused slots hold 0 and are never read by the kernel.
+ *   seg_ptr    uint32 [n_kblocks][n_pad]  where the lists of (kb, n) start in `stream`, in units
+ *                                         of `chunk` int32 slots
+ *   stream     int32  [stream_len]        K-block after K-block, inside a block column after
+ *                                         column: the +1 rows of (kb, n) as block-local row
+ *                                         numbers (row - kb*k_block), then the -1 rows, each list
+ *                                         stored in chunks of `chunk` slots.  Full chunks come
+ *                                         first.  A last partial chunk with r entries (binary
+ *                                         r = 4a+2b+c) keeps 4a entries in slots 0..3, 2b in slots
+ *                                         4..5, c in slot 6; unused slots hold 0 and are never
+ *                                         used by the kernel.
+ *   workspace  bytes  [workspace_bytes]   split-K partial sums and arrival counters of tstgemm()
  * n_pad = N rounded up to a multiple of 64; columns >= N have empty lists.
  */
 typedef struct tcsc_layout {
     int32_t K, N, n_pad, k_block, n_kblocks, chunk;
     int64_t nnz_pos, nnz_neg, stream_len;
     size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
-    size_t off_seg_count, off_col_ptr, off_stream, total_bytes;
+    size_t off_seg_count, off_seg_ptr, off_stream, off_workspace, workspace_bytes, total_bytes;
 } tcsc_layout_t;
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);
@@ -114,10 +118,21 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * M >= 1 arbitrary; K, N must equal the handle's.  Asynchronous: the kernels are enqueued on
  * `stream` (a hipStream_t, NULL = null stream), no host synchronisation, no allocation.
  * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, EHIP (launch failure).
- * Rounding: fp32 accumulation in an order fixed by (M, K, N) and the matrix; repeated calls
- * give bit-identical results.  Integer-valued inputs small enough for fp32 give exact results.
+ * Rounding: fp32 accumulation in an order fixed by (M, K, N), the matrix and the tuning
+ * parameters; repeated calls give bit-identical results.  Integer-valued inputs small enough
+ * for fp32 give exact results.
+ * Two calls that use the same handle must be ordered (same stream, or an event between them):
+ * they share the handle's split-K workspace.
  */
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
+
+/*
+ * Launch-shape overrides for the large-M kernel, for tuning runs: columns per wavefront
+ * (1, 2 or 4) and number of K slices (1..8) computed by different workgroups and summed in a
+ * fixed order.  0 restores the built-in choice for that parameter.  Process-wide.
+ * Errors: EINVAL for a value outside the ranges above.
+ */
+int tstgemm_set_tuning(int cols_per_wave, int k_slices);
 
 /* Release the handle and its host arrays (not the device buffer).  NULL is allowed. */
 void tcsc_destroy(tcsc_t *t);

@@ -27,7 +27,8 @@ class TcscLayout(ctypes.Structure):
                 ("nnz_pos", ctypes.c_int64), ("nnz_neg", ctypes.c_int64), ("stream_len", ctypes.c_int64),
                 ("off_col_start_pos", ctypes.c_size_t), ("off_col_start_neg", ctypes.c_size_t),
                 ("off_row_index_pos", ctypes.c_size_t), ("off_row_index_neg", ctypes.c_size_t),
-                ("off_seg_count", ctypes.c_size_t), ("off_col_ptr", ctypes.c_size_t), ("off_stream", ctypes.c_size_t),
+                ("off_seg_count", ctypes.c_size_t), ("off_seg_ptr", ctypes.c_size_t), ("off_stream", ctypes.c_size_t),
+                ("off_workspace", ctypes.c_size_t), ("workspace_bytes", ctypes.c_size_t),
                 ("total_bytes", ctypes.c_size_t)]
 
 
@@ -62,6 +63,8 @@ def _load():
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
     lib.tcsc_strerror.restype = ctypes.c_char_p
+    lib.tstgemm_set_tuning.argtypes = [ci, ci]
+    lib.tstgemm_set_tuning.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm"):
         getattr(lib, name).restype = ci
@@ -173,7 +176,7 @@ def tcsc_layout(t: Tcsc) -> TcscLayout:
 def _stream_ptr(stream):
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
+    return s.cuda_stream
 
 
 def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
@@ -183,30 +186,46 @@ def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
     with torch.cuda.device(dev):
         buf = torch.empty(tcsc_device_bytes(t) + 256, dtype=torch.uint8, device=dev)
         base = (buf.data_ptr() + 255) // 256 * 256
-        _check(_load().tcsc_upload(t.handle, ctypes.c_void_p(base), tcsc_device_bytes(t), _stream_ptr(stream)),
-               "tcsc_upload")
+        _check(_load().tcsc_upload(t.handle, base, tcsc_device_bytes(t), _stream_ptr(stream)), "tcsc_upload")
     t.device_buffer = buf
     t.device_base = base
+    t.device_index = buf.device.index
     return t
 
 
 def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None):
-    """Y = X W + b on the GPU.  X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None."""
+    """Y = X W + b on the GPU.  X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None.
+
+    Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
+    handle was uploaded to and the one holding X, b and Y."""
     import torch
-    if not (X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.dim() == 2):
+    f32 = torch.float32
+    if not (X.is_cuda and X.dtype == f32 and X.dim() == 2 and X.is_contiguous()):
         raise ValueError("X must be a contiguous float32 CUDA matrix")
     M, K = X.shape
-    if b is not None and not (b.is_cuda and b.dtype == torch.float32 and b.is_contiguous() and b.numel() == t.N):
-        raise ValueError("b must be a contiguous float32 CUDA vector of length N")
+    N = t.N
+    dev = X.device.index
+    if dev != getattr(t, "device_index", dev) or dev != torch.cuda.current_device():
+        raise ValueError("X, the uploaded handle and the current device must be the same GPU")
+    if b is None:
+        b_ptr = None
+    elif b.is_cuda and b.dtype == f32 and b.is_contiguous() and b.numel() == N and b.device.index == dev:
+        b_ptr = b.data_ptr()
+    else:
+        raise ValueError("b must be a contiguous float32 CUDA vector of length N on X's device")
     if Y is None:
-        Y = torch.empty((M, t.N), dtype=torch.float32, device=X.device)
-    elif not (Y.is_cuda and Y.dtype == torch.float32 and Y.is_contiguous() and tuple(Y.shape) == (M, t.N)):
-        raise ValueError("Y must be a contiguous float32 CUDA matrix of shape [M, N]")
-    with torch.cuda.device(X.device):
-        _check(_load().tstgemm(ctypes.c_void_p(X.data_ptr()), t.handle,
-                               None if b is None else ctypes.c_void_p(b.data_ptr()), ctypes.c_void_p(Y.data_ptr()),
-                               int(M), int(K), int(t.N), _stream_ptr(stream)), "tstgemm")
+        Y = torch.empty((M, N), dtype=f32, device=X.device)
+    elif not (Y.is_cuda and Y.dtype == f32 and Y.dim() == 2 and Y.shape[0] == M and Y.shape[1] == N
+              and Y.is_contiguous() and Y.device.index == dev):
+        raise ValueError("Y must be a contiguous float32 CUDA matrix of shape [M, N] on X's device")
+    rc = _load().tstgemm(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if rc != 0:
+        raise TstgemmError(rc, "tstgemm")
     return Y
+
+
+def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0):
+    _check(_load().tstgemm_set_tuning(int(cols_per_wave), int(k_slices)), "tstgemm_set_tuning")
 
 
 def tcsc_destroy(t: Tcsc):

@@ -53,8 +53,10 @@ void compute_layout(tcsc *t)
     l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + 4));
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + 4));
     l.off_seg_count = place(sizeof(int32_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
-    l.off_col_ptr = place(sizeof(int64_t) * (size_t)(l.n_pad + 1));
-    l.off_stream = place(sizeof(int32_t) * (size_t)(len + tst::kChunk));
+    l.off_seg_ptr = place(sizeof(uint32_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
+    l.off_stream = place(sizeof(int32_t) * (size_t)(len + tst::kStreamSlack));
+    l.off_workspace = place(tst::kWorkspaceBytes);
+    l.workspace_bytes = tst::kWorkspaceBytes;
     l.total_bytes = off;
 }
 
@@ -224,6 +226,7 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
     if (copy(l.off_row_index_neg, t->row_index_neg) != hipSuccess) return TSTGEMM_EHIP;
     // The sources are pageable host memory: wait until the copies have read them.
     if (hipStreamSynchronize(s) != hipSuccess) return TSTGEMM_EHIP;
+    if (hipMemsetAsync(d + l.off_workspace, 0, tst::kCounterBytes, s) != hipSuccess) return TSTGEMM_EHIP;
     if (tst::launch_reblock(t, s) != hipSuccess) return TSTGEMM_EHIP;
     t->uploaded = true;
     return TSTGEMM_OK;
@@ -238,6 +241,15 @@ int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, in
     hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, Y, M, s)
                                                : tst::launch_large(X, t, b, Y, M, s);
     return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
+}
+
+int tstgemm_set_tuning(int cols_per_wave, int k_slices)
+{
+    if (cols_per_wave != 0 && cols_per_wave != 1 && cols_per_wave != 2 && cols_per_wave != 4) return TSTGEMM_EINVAL;
+    if (k_slices < 0 || k_slices > 8) return TSTGEMM_EINVAL;
+    tst::g_cols_per_wave = cols_per_wave;
+    tst::g_k_slices = k_slices;
+    return TSTGEMM_OK;
 }
 
 void tcsc_destroy(tcsc_t *t) { delete t; }

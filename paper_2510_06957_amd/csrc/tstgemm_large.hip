@@ -13,69 +13,132 @@
 //     the gather of one index is a single conflict-free ds_read (b32/b64/b128) per lane;
 //   * the next block's tile is fetched from global memory into registers while the current one
 //     is consumed, and written to the second LDS buffer afterwards (one barrier per block);
-//   * accumulators stay in VGPRs over all K-blocks; the bias add and the store are fused.
+//   * accumulators stay in VGPRs over all K-blocks of the workgroup's K slice; the bias add and
+//     the store are fused;
+//   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
+//     8 slices handled by different workgroups; each writes its partial sums to the workspace,
+//     and the workgroup that arrives last adds the slices in slice order, adds the bias and
+//     stores Y -- a fixed summation order, so results do not depend on timing.
 //
-// Index lists come from the K-blocked stream written by the re-blocking pass: per column and
-// K-block a +1 list and a -1 list in 8-slot chunks, fetched with 32-byte scalar loads.
+// Index lists come from the K-blocked stream written by the re-blocking pass: per K-block and
+// column a +1 list and a -1 list in 8-slot chunks.  The lists of a wavefront's columns are
+// contiguous, so the wavefront fetches them as one 1 KiB window (16 bytes per lane, one vector
+// load) a whole K-block ahead and then broadcasts one index at a time out of the window into a
+// scalar register (v_readlane): no memory latency sits between two gathers.  The list lengths
+// and the window position travel the same way, two K-blocks ahead.
 #include "tstgemm_internal.h"
 
 namespace tst {
+
+int g_cols_per_wave = 0, g_k_slices = 0;
+
 namespace {
 
-typedef int int8v __attribute__((ext_vector_type(8)));
+constexpr int NW = 16;   // wavefronts per workgroup
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
 
 template <int R> struct RowVec;
 template <> struct RowVec<1> { typedef float type; };
 template <> struct RowVec<2> { typedef float __attribute__((ext_vector_type(2))) type; };
 template <> struct RowVec<4> { typedef float __attribute__((ext_vector_type(4))) type; };
-typedef float float4v __attribute__((ext_vector_type(4)));
 
 template <int R> __device__ __forceinline__ float lane_of(const typename RowVec<R>::type &v, int r)
 {
     if constexpr (R == 1) return v; else return v[r];
 }
+template <int R> __device__ __forceinline__ typename RowVec<R>::type zero_vec()
+{
+    if constexpr (R == 1) return 0.f; else return typename RowVec<R>::type(0.f);
+}
 
-// acc (+/-)= tile[idx][rows of this lane]
-template <int R, bool NEG>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile_lane, int idx)
+// acc (+/-)= tile[idx[i]][rows of this lane], i < COUNT.  All gathers are issued before the first addition so that
+// COUNT LDS reads are in flight at once.
+template <int R, bool NEG, int COUNT>
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile_lane, const int (&idx)[COUNT])
 {
     typedef typename RowVec<R>::type V;
-    const V v = *reinterpret_cast<const V *>(tile_lane + idx * (64 * R * 4));
-    if constexpr (NEG) acc -= v; else acc += v;
+    V v[COUNT];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < COUNT; ++i) v[i] = *reinterpret_cast<const V *>(tile_lane + idx[i] * (64 * R * 4));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < COUNT; ++i) {
+        if constexpr (NEG) acc -= v[i]; else acc += v[i];
+    }
 }
 
-// One list (n entries, stored in chunks of 8 slots at p; p and n are wave-uniform).
-template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, const int32_t *__restrict__ p, int n,
-                                         const char *tile_lane)
+constexpr int kWindowChunks = 32;                       // chunks per window: 64 lanes x 4 slots
+constexpr int kWindowSlots = kWindowChunks * kChunk;
+
+// The 1 KiB of index stream starting at wp, four consecutive slots per lane.
+__device__ __forceinline__ int4v load_window(const int32_t *wp, int lane)
 {
+    return *reinterpret_cast<const int4v *>(wp + 4 * lane);
+}
+
+// One list of n entries starting at chunk `cc` of the window `win` (which starts at wp in the stream); on return cc
+// is the chunk behind the list.  A chunk's slots 0..3 sit in lane 2*cc, slots 4..7 in lane 2*cc+1.  n, cc, wp are
+// wave-uniform.
+template <int R, bool NEG>
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, int n, int &cc, int4v &win,
+                                         const int32_t *__restrict__ &wp, int lane, const char *tile_lane)
+{
+    auto next_window = [&]() {   // rare: the wavefront's lists of this K-block exceed one window
+        wp += kWindowSlots;
+        win = load_window(wp, lane);
+        cc = 0;
+    };
     while (n >= kChunk) {
-        const int8v c = *reinterpret_cast<const int8v *>(p);
+        if (__builtin_expect(cc == kWindowChunks, 0)) next_window();
+        const int l0 = 2 * cc, l1 = l0 + 1;
+        int idx[kChunk];
 #pragma unroll
-        for (int i = 0; i < kChunk; ++i) gather<R, NEG>(acc, tile_lane, c[i]);
-        p += kChunk;
+        for (int i = 0; i < 4; ++i) {
+            idx[i] = __builtin_amdgcn_readlane(win[i], l0);
+            idx[4 + i] = __builtin_amdgcn_readlane(win[i], l1);
+        }
+        gather<R, NEG, kChunk>(acc, tile_lane, idx);
         n -= kChunk;
+        ++cc;
     }
     if (n > 0) {   // partial chunk: 4 entries in slots 0..3 if n&4, 2 in slots 4..5 if n&2, 1 in slot 6 if n&1
-        const int8v c = *reinterpret_cast<const int8v *>(p);
+        if (__builtin_expect(cc == kWindowChunks, 0)) next_window();
+        const int l0 = 2 * cc, l1 = l0 + 1;
         if (n & 4) {
+            int idx[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) gather<R, NEG>(acc, tile_lane, c[i]);
+            for (int i = 0; i < 4; ++i) idx[i] = __builtin_amdgcn_readlane(win[i], l0);
+            gather<R, NEG, 4>(acc, tile_lane, idx);
         }
         if (n & 2) {
-            gather<R, NEG>(acc, tile_lane, c[4]);
-            gather<R, NEG>(acc, tile_lane, c[5]);
+            const int idx[2] = {__builtin_amdgcn_readlane(win[0], l1), __builtin_amdgcn_readlane(win[1], l1)};
+            gather<R, NEG, 2>(acc, tile_lane, idx);
         }
-        if (n & 1) gather<R, NEG>(acc, tile_lane, c[6]);
+        if (n & 1) {
+            const int idx[1] = {__builtin_amdgcn_readlane(win[2], l1)};
+            gather<R, NEG, 1>(acc, tile_lane, idx);
+        }
+        ++cc;
     }
 }
 
-// R rows per lane, NW wavefronts per workgroup, NCW columns per wavefront.
-template <int R, int NW, int NCW>
-__global__ void __launch_bounds__(NW * 64)
-k_large(const float *__restrict__ X, const int32_t *__restrict__ seg_count, const int64_t *__restrict__ col_ptr,
-        const int32_t *__restrict__ stream, const float *__restrict__ b, float *__restrict__ Y, int M, int K, int N,
-        int n_pad, int n_kblocks, int n_colgroups)
+struct LargeArgs {
+    const float *X;
+    const int32_t *seg_count;
+    const uint32_t *seg_ptr;
+    const int32_t *stream;
+    const float *b;
+    float *Y;
+    float *partials;
+    int32_t *counters;
+    int M, K, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
+};
+
+// R rows per lane, NCW columns per wavefront.
+template <int R, int NCW>
+__global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
     constexpr int TM = 64 * R;            // rows of X per workgroup tile
@@ -86,12 +149,21 @@ k_large(const float *__restrict__ X, const int32_t *__restrict__ seg_count, cons
     static_assert(CPT >= 1 && CPT * NT == TM * (kKBlock / 4), "staging must tile the block exactly");
 
     __shared__ __attribute__((aligned(16))) char lds[2 * TILE];
+    __shared__ int last_flag;
+
+    const float *__restrict__ X = a.X;
+    const int32_t *__restrict__ stream = a.stream;
+    const int M = a.M, K = a.K, N = a.N, n_pad = a.n_pad;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int cg = blockIdx.x % n_colgroups, mt = blockIdx.x / n_colgroups;
+    const int cg = blockIdx.x % a.n_colgroups;
+    const int rest = blockIdx.x / a.n_colgroups;
+    const int slice = rest % a.k_slices, mt = rest / a.k_slices;
     const int m0 = mt * TM;
     const int c0 = (cg * NW + wave) * NCW;   // < n_pad by construction of the grid
+    const int kb0 = min(slice * a.kb_per_slice, a.n_kblocks);
+    const int kb1 = min(kb0 + a.kb_per_slice, a.n_kblocks);
 
     // ---- staging role of this thread: row `srow` of the tile, k-segment `sseg`
     const int srow = threadIdx.x % TM, sseg = threadIdx.x / TM;
@@ -128,45 +200,102 @@ k_large(const float *__restrict__ X, const int32_t *__restrict__ seg_count, cons
 
     // ---- compute role: columns c0 .. c0+NCW-1, rows m0 + R*lane .. + R-1
     V acc[NCW];
-    const int32_t *sp[NCW];
 #pragma unroll
-    for (int j = 0; j < NCW; ++j) {
-        if constexpr (R == 1) acc[j] = 0.f; else acc[j] = V(0.f);
-        sp[j] = stream + col_ptr[c0 + j];
+    for (int j = 0; j < NCW; ++j) acc[j] = zero_vec<R>();
+
+    if (kb0 < kb1) {
+        // List lengths and window position of (kb, c0 .. c0+NCW-1) come through vector loads: lane j (mod NCW) holds
+        // the packed counts of column c0+j, every lane the position of the first chunk.
+        const size_t meta_lane = (size_t)c0 + (lane & (NCW - 1));
+        auto load_cnt = [&](int kb) { return a.seg_count[(size_t)kb * n_pad + meta_lane]; };
+        auto load_ptr = [&](int kb) { return (int)a.seg_ptr[(size_t)kb * n_pad + c0]; };
+        int vcnt = load_cnt(kb0), vptr = load_ptr(kb0);
+        stage_load(kb0);
+        int cnt[NCW];
+#pragma unroll
+        for (int j = 0; j < NCW; ++j) cnt[j] = __builtin_amdgcn_readlane(vcnt, j);
+        const int32_t *__restrict__ wp = stream + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(vptr) * kChunk;
+        int4v win = load_window(wp, lane);
+        if (kb0 + 1 < kb1) {
+            vcnt = load_cnt(kb0 + 1);
+            vptr = load_ptr(kb0 + 1);
+        }
+        stage_store(0);
+        __syncthreads();
+
+        for (int kb = kb0; kb < kb1; ++kb) {
+            const bool more = kb + 1 < kb1;
+            int cnt_next[NCW];
+            const int32_t *__restrict__ wp_next = stream;
+            int4v win_next = {0, 0, 0, 0};
+            if (more) {
+                stage_load(kb + 1);
+#pragma unroll
+                for (int j = 0; j < NCW; ++j) cnt_next[j] = __builtin_amdgcn_readlane(vcnt, j);
+                wp_next = stream + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(vptr) * kChunk;
+                win_next = load_window(wp_next, lane);
+                if (kb + 2 < kb1) {
+                    vcnt = load_cnt(kb + 2);
+                    vptr = load_ptr(kb + 2);
+                }
+            }
+            const char *tile_lane = lds + ((kb - kb0) & 1) * TILE + lane * (R * 4);
+            int cc = 0;
+#pragma unroll
+            for (int j = 0; j < NCW; ++j) {
+                run_list<R, false>(acc[j], cnt[j] & 0xffff, cc, win, wp, lane, tile_lane);
+                run_list<R, true>(acc[j], (cnt[j] >> 16) & 0xffff, cc, win, wp, lane, tile_lane);
+            }
+            if (more) {
+                wp = wp_next;
+                win = win_next;
+#pragma unroll
+                for (int j = 0; j < NCW; ++j) cnt[j] = cnt_next[j];
+                stage_store((kb + 1 - kb0) & 1);
+            }
+            __syncthreads();
+        }
     }
 
-    stage_load(0);
-    stage_store(0);
-    __syncthreads();
-
-    for (int kb = 0; kb < n_kblocks; ++kb) {
-        const bool more = kb + 1 < n_kblocks;
-        if (more) stage_load(kb + 1);
-        const char *tile_lane = lds + (kb & 1) * TILE + lane * (R * 4);
-        const int32_t *cnt = seg_count + (size_t)kb * n_pad + c0;
+    // ---- split K: publish this slice's partial sums; the last workgroup of the group sums all slices in order
+    if (a.k_slices > 1) {
+        const int group = mt * a.n_colgroups + cg;
+        constexpr size_t kSliceFloats = (size_t)NW * NCW * TM;
+        float *gbase = a.partials + (size_t)group * a.k_slices * kSliceFloats + (size_t)(wave * NCW) * TM + lane * R;
+#pragma unroll
+        for (int j = 0; j < NCW; ++j)
+            *reinterpret_cast<V *>(gbase + (size_t)slice * kSliceFloats + (size_t)j * TM) = acc[j];
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int arrived = atomicAdd(&a.counters[group], 1);
+            const int last = arrived == a.k_slices - 1;
+            if (last) a.counters[group] = 0;   // ready for the next call
+            last_flag = last;
+        }
+        __syncthreads();
+        if (!last_flag) return;
+        __threadfence();
 #pragma unroll
         for (int j = 0; j < NCW; ++j) {
-            const int c = cnt[j];
-            const int np = c & 0xffff, nn = (c >> 16) & 0xffff;
-            run_list<R, false>(acc[j], sp[j], np, tile_lane);
-            sp[j] += (np + kChunk - 1) & ~(kChunk - 1);
-            run_list<R, true>(acc[j], sp[j], nn, tile_lane);
-            sp[j] += (nn + kChunk - 1) & ~(kChunk - 1);
+            V sum = zero_vec<R>();
+            for (int s = 0; s < a.k_slices; ++s)
+                sum += *reinterpret_cast<const V *>(gbase + (size_t)s * kSliceFloats + (size_t)j * TM);
+            acc[j] = sum;
         }
-        if (more) stage_store((kb + 1) & 1);
-        __syncthreads();
     }
 
     // ---- epilogue: Y = acc + b, bias added once, last
     float bias[NCW];
 #pragma unroll
-    for (int j = 0; j < NCW; ++j) bias[j] = (b != nullptr && c0 + j < N) ? b[c0 + j] : 0.f;
-    const bool store_vec = NCW == 4 && (N % 4 == 0) && (c0 + 4 <= N) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+    for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
+    const bool store_vec =
+        NCW == 4 && (N % 4 == 0) && (c0 + 4 <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int m = m0 + lane * R + r;
         if (m >= M) continue;
-        float *yrow = Y + (size_t)m * N + c0;
+        float *yrow = a.Y + (size_t)m * N + c0;
         if constexpr (NCW == 4) {
             if (store_vec) {
                 float4v o;
@@ -182,30 +311,63 @@ k_large(const float *__restrict__ X, const int32_t *__restrict__ seg_count, cons
     }
 }
 
-template <int R, int NW, int NCW>
-hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+template <int R, int NCW>
+hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M, int k_slices, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
     constexpr int TM = 64 * R;
-    const int n_colgroups = l.n_pad / (NW * NCW);
-    const int m_tiles = (M + TM - 1) / TM;
-    const long long grid = (long long)n_colgroups * m_tiles;
+    LargeArgs a;
+    a.X = X; a.seg_count = d.seg_count; a.seg_ptr = d.seg_ptr; a.stream = d.stream; a.b = b; a.Y = Y;
+    a.partials = d.partials; a.counters = d.counters;
+    a.M = M; a.K = l.K; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
+    a.n_colgroups = l.n_pad / (NW * NCW);
+    const long long m_tiles = (M + TM - 1) / TM;
+    const long long groups = m_tiles * a.n_colgroups;
+    if (k_slices > 1 && groups * k_slices > kMaxSplitGroups) k_slices = (int)(kMaxSplitGroups / groups);
+    if (k_slices < 1) k_slices = 1;
+    a.k_slices = k_slices;
+    a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
+    const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_large<R, NW, NCW>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, X, d.seg_count, d.col_ptr,
-                       d.stream, b, Y, M, l.K, l.N, l.n_pad, l.n_kblocks, n_colgroups);
+    hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
-// Columns per wavefront: as many as still leave about two workgroups per compute unit.
+// Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave
+// compute units idle, into as few slices as fill them.
 template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
 {
-    constexpr int NW = 16;
+    const tcsc_layout_t &l = t->layout;
+    const int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
     const long long m_tiles = (M + 64 * R - 1) / (64 * R);
-    const long long target = 512;
-    if (m_tiles * (t->layout.n_pad / (NW * 4)) >= target) return launch<R, NW, 4>(X, t, b, Y, M, stream);
-    if (m_tiles * (t->layout.n_pad / (NW * 2)) >= target) return launch<R, NW, 2>(X, t, b, Y, M, stream);
-    return launch<R, NW, 1>(X, t, b, Y, M, stream);
+    const long long groups = m_tiles * (l.n_pad / (NW * ncw));
+    int k_slices = g_k_slices;
+    if (k_slices == 0) {
+        const int cus = compute_units();
+        k_slices = groups >= cus ? 1 : (int)((cus + groups - 1) / groups);
+        if (k_slices > 8) k_slices = 8;
+    }
+    if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;
+    switch (ncw) {
+    case 1: return launch<R, 1>(X, t, b, Y, M, k_slices, stream);
+    case 2: return launch<R, 2>(X, t, b, Y, M, k_slices, stream);
+    default: return launch<R, 4>(X, t, b, Y, M, k_slices, stream);
+    }
 }
 
 }  // namespace

@@ -55,7 +55,7 @@ def decode_device_form(t):
     canon = (view(lay.off_col_start_pos, lay.N + 1, np.int32), view(lay.off_col_start_neg, lay.N + 1, np.int32),
              view(lay.off_row_index_pos, lay.nnz_pos, np.int32), view(lay.off_row_index_neg, lay.nnz_neg, np.int32))
     seg = view(lay.off_seg_count, lay.n_kblocks * lay.n_pad, np.int32).reshape(lay.n_kblocks, lay.n_pad)
-    col_ptr = view(lay.off_col_ptr, lay.n_pad + 1, np.int64)
+    seg_ptr = view(lay.off_seg_ptr, lay.n_kblocks * lay.n_pad, np.uint32).reshape(lay.n_kblocks, lay.n_pad)
     stream = view(lay.off_stream, lay.stream_len, np.int32)
     W = np.zeros((lay.K, lay.N), np.int8)
     C = lay.chunk
@@ -74,22 +74,19 @@ def decode_device_form(t):
                 vals.append(ch[6])
         return np.array(vals, dtype=np.int64), pos + (count + C - 1) // C * C
 
-    for n in range(lay.n_pad):
-        pos = int(col_ptr[n])
-        for kb in range(lay.n_kblocks):
+    pos = 0   # lists are stored K-block after K-block, column after column, without gaps
+    for kb in range(lay.n_kblocks):
+        for n in range(lay.n_pad):
             c = int(seg[kb, n])
             cp, cn = c & 0xffff, (c >> 16) & 0xffff
+            assert int(seg_ptr[kb, n]) * C == pos
             if n >= lay.N:
                 assert c == 0
                 continue
-            rows, pos = read_list(pos, cp)
-            assert rows.size == 0 or (rows.min() >= 0 and rows.max() < lay.k_block and np.all(np.diff(rows) > 0))
-            assert np.all(W[kb * lay.k_block + rows, n] == 0)
-            W[kb * lay.k_block + rows, n] = 1
-            rows, pos = read_list(pos, cn)
-            assert rows.size == 0 or (rows.min() >= 0 and rows.max() < lay.k_block and np.all(np.diff(rows) > 0))
-            assert np.all(W[kb * lay.k_block + rows, n] == 0)
-            W[kb * lay.k_block + rows, n] = -1
-        assert pos == int(col_ptr[n + 1])
-    assert int(col_ptr[lay.n_pad]) == lay.stream_len
+            for count, sign in ((cp, 1), (cn, -1)):
+                rows, pos = read_list(pos, count)
+                assert rows.size == 0 or (rows.min() >= 0 and rows.max() < lay.k_block and np.all(np.diff(rows) > 0))
+                assert np.all(W[kb * lay.k_block + rows, n] == 0)
+                W[kb * lay.k_block + rows, n] = sign
+    assert pos == lay.stream_len
     return W, canon

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(str(tg.library_path()))
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-            "tcsc_layout", "tcsc_upload", "tstgemm", "tcsc_destroy", "tcsc_strerror"} <= names
+            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tcsc_destroy", "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
 
@@ -118,7 +118,8 @@ def test_layout_bookkeeping():
             expect += int((-(-cnt // 8) * 8).sum())
     assert lay.stream_len == expect
     offs = [lay.off_col_start_pos, lay.off_col_start_neg, lay.off_row_index_pos, lay.off_row_index_neg,
-            lay.off_seg_count, lay.off_col_ptr, lay.off_stream, lay.total_bytes]
+            lay.off_seg_count, lay.off_seg_ptr, lay.off_stream, lay.off_workspace, lay.total_bytes]
     assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
     assert lay.total_bytes == tg.tcsc_device_bytes(t)
-    assert lay.total_bytes - lay.off_stream >= 4 * lay.stream_len
+    assert lay.off_workspace - lay.off_stream >= 4 * lay.stream_len
+    assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
