@@ -70,7 +70,6 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char
 }
 
 constexpr int kWindowChunks = 32;                       // chunks per window: 64 lanes x 4 slots
-constexpr int kWindowSlots = kWindowChunks * kChunk;
 
 // The 1 KiB of index stream starting at wp, four consecutive slots per lane.
 __device__ __forceinline__ int4v load_window(const int32_t *wp, int lane)
@@ -78,47 +77,52 @@ __device__ __forceinline__ int4v load_window(const int32_t *wp, int lane)
     return *reinterpret_cast<const int4v *>(wp + 4 * lane);
 }
 
-// One list of n entries starting at chunk `cc` of the window `win` (which starts at wp in the stream); on return cc
-// is the chunk behind the list.  A chunk's slots 0..3 sit in lane 2*cc, slots 4..7 in lane 2*cc+1.  n, cc, wp are
-// wave-uniform.
-template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, int n, int &cc, int4v &win,
-                                         const int32_t *__restrict__ &wp, int lane, const char *tile_lane)
+// The eight slots of chunk cc of the window: slots 0..3 sit in lane 2*cc, slots 4..7 in lane 2*cc+1.  Chunks behind
+// the window (a wavefront whose lists of one K-block exceed 1 KiB: rare) are read straight from the stream with a
+// scalar load.  cc and wp are wave-uniform.
+__device__ __forceinline__ void chunk_slots(int (&idx)[kChunk], const int4v &win, const int32_t *__restrict__ wp, int cc)
 {
-    auto next_window = [&]() {   // rare: the wavefront's lists of this K-block exceed one window
-        wp += kWindowSlots;
-        win = load_window(wp, lane);
-        cc = 0;
-    };
-    while (n >= kChunk) {
-        if (__builtin_expect(cc == kWindowChunks, 0)) next_window();
+    if (__builtin_expect(cc < kWindowChunks, 1)) {
         const int l0 = 2 * cc, l1 = l0 + 1;
-        int idx[kChunk];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             idx[i] = __builtin_amdgcn_readlane(win[i], l0);
             idx[4 + i] = __builtin_amdgcn_readlane(win[i], l1);
         }
+    } else {
+        const int32_t *p = wp + (size_t)cc * kChunk;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) idx[i] = p[i];
+    }
+}
+
+// One list of n entries starting at chunk `cc` of the window `win` (which starts at wp in the stream); on return cc
+// is the chunk behind the list.  n and cc are wave-uniform.
+template <int R, bool NEG>
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, int n, int &cc, const int4v &win,
+                                         const int32_t *__restrict__ wp, const char *tile_lane)
+{
+    while (n >= kChunk) {
+        int idx[kChunk];
+        chunk_slots(idx, win, wp, cc);
         gather<R, NEG, kChunk>(acc, tile_lane, idx);
         n -= kChunk;
         ++cc;
     }
     if (n > 0) {   // partial chunk: 4 entries in slots 0..3 if n&4, 2 in slots 4..5 if n&2, 1 in slot 6 if n&1
-        if (__builtin_expect(cc == kWindowChunks, 0)) next_window();
-        const int l0 = 2 * cc, l1 = l0 + 1;
+        int idx[kChunk];
+        chunk_slots(idx, win, wp, cc);
         if (n & 4) {
-            int idx[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) idx[i] = __builtin_amdgcn_readlane(win[i], l0);
-            gather<R, NEG, 4>(acc, tile_lane, idx);
+            const int four[4] = {idx[0], idx[1], idx[2], idx[3]};
+            gather<R, NEG, 4>(acc, tile_lane, four);
         }
         if (n & 2) {
-            const int idx[2] = {__builtin_amdgcn_readlane(win[0], l1), __builtin_amdgcn_readlane(win[1], l1)};
-            gather<R, NEG, 2>(acc, tile_lane, idx);
+            const int two[2] = {idx[4], idx[5]};
+            gather<R, NEG, 2>(acc, tile_lane, two);
         }
         if (n & 1) {
-            const int idx[1] = {__builtin_amdgcn_readlane(win[2], l1)};
-            gather<R, NEG, 1>(acc, tile_lane, idx);
+            const int one[1] = {idx[6]};
+            gather<R, NEG, 1>(acc, tile_lane, one);
         }
         ++cc;
     }
@@ -136,8 +140,9 @@ struct LargeArgs {
     int M, K, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
 };
 
-// R rows per lane, NCW columns per wavefront.
-template <int R, int NCW>
+// R rows per lane, NCW columns per wavefront; VEC: X rows are 16-byte aligned and K is a multiple of 4, so X is
+// staged with 16-byte loads (otherwise element by element).
+template <int R, int NCW, bool VEC>
 __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
@@ -168,23 +173,27 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
     // ---- staging role of this thread: row `srow` of the tile, k-segment `sseg`
     const int srow = threadIdx.x % TM, sseg = threadIdx.x / TM;
     const int gm = m0 + srow;
-    const float *xrow = X + (size_t)(gm < M ? gm : 0) * K;
-    const bool vec_ok = (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const bool row_ok = gm < M;
+    const float *xrow = X + (size_t)(row_ok ? gm : M - 1) * K;
     float4v st[CPT];
 
+    // All loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are
+    // zeroed afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
     auto stage_load = [&](int kb) {
         const int k0 = kb * kKBlock + sseg * (4 * CPT);
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int k = k0 + 4 * i;
-            float4v v = {0.f, 0.f, 0.f, 0.f};
-            if (gm < M) {
-                if (vec_ok && k + 4 <= K) {
-                    v = *reinterpret_cast<const float4v *>(xrow + k);
-                } else {
+            float4v v;
+            if constexpr (VEC) {
+                const bool ok = row_ok && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
+                v = *reinterpret_cast<const float4v *>(xrow + (k < K ? k : 0));
+                if (!ok) v = float4v{0.f, 0.f, 0.f, 0.f};
+            } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (k + j < K) v[j] = xrow[k + j];
+                for (int j = 0; j < 4; ++j) {
+                    const float x = xrow[k + j < K ? k + j : 0];
+                    v[j] = (row_ok && k + j < K) ? x : 0.f;
                 }
             }
             st[i] = v;
@@ -204,55 +213,49 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
     for (int j = 0; j < NCW; ++j) acc[j] = zero_vec<R>();
 
     if (kb0 < kb1) {
-        // List lengths and window position of (kb, c0 .. c0+NCW-1) come through vector loads: lane j (mod NCW) holds
-        // the packed counts of column c0+j, every lane the position of the first chunk.
-        const size_t meta_lane = (size_t)c0 + (lane & (NCW - 1));
-        auto load_cnt = [&](int kb) { return a.seg_count[(size_t)kb * n_pad + meta_lane]; };
-        auto load_ptr = [&](int kb) { return (int)a.seg_ptr[(size_t)kb * n_pad + c0]; };
-        int vcnt = load_cnt(kb0), vptr = load_ptr(kb0);
+        // List lengths and window position of (kb, c0 .. c0+NCW-1) come through ONE vector load: lane j < NCW reads
+        // the packed counts of column c0+j, lane NCW the position of the first chunk (the pattern repeats every
+        // 2*NCW lanes).  A scalar load would share its wait counter with the LDS gathers.
+        const int32_t *meta_base = (lane & NCW) ? reinterpret_cast<const int32_t *>(a.seg_ptr) + c0
+                                                : a.seg_count + c0 + (lane & (NCW - 1));
+        auto load_meta = [&](int kb) { return meta_base[(size_t)kb * n_pad]; };
+        auto clamp_kb = [&](int kb) { return kb < kb1 ? kb : kb1 - 1; };
+        int meta = load_meta(kb0);
         stage_load(kb0);
         int cnt[NCW];
 #pragma unroll
-        for (int j = 0; j < NCW; ++j) cnt[j] = __builtin_amdgcn_readlane(vcnt, j);
-        const int32_t *__restrict__ wp = stream + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(vptr) * kChunk;
+        for (int j = 0; j < NCW; ++j) cnt[j] = __builtin_amdgcn_readlane(meta, j);
+        const int32_t *__restrict__ wp = stream + (size_t)(uint32_t)__builtin_amdgcn_readlane(meta, NCW) * kChunk;
         int4v win = load_window(wp, lane);
-        if (kb0 + 1 < kb1) {
-            vcnt = load_cnt(kb0 + 1);
-            vptr = load_ptr(kb0 + 1);
-        }
+        meta = load_meta(clamp_kb(kb0 + 1));
         stage_store(0);
         __syncthreads();
 
         for (int kb = kb0; kb < kb1; ++kb) {
+            // requests for the next K-block (tile, window) and the one after it (list lengths, window position);
+            // behind the last block they repeat the last one and are not used
             const bool more = kb + 1 < kb1;
+            stage_load(clamp_kb(kb + 1));
             int cnt_next[NCW];
-            const int32_t *__restrict__ wp_next = stream;
-            int4v win_next = {0, 0, 0, 0};
-            if (more) {
-                stage_load(kb + 1);
 #pragma unroll
-                for (int j = 0; j < NCW; ++j) cnt_next[j] = __builtin_amdgcn_readlane(vcnt, j);
-                wp_next = stream + (size_t)(uint32_t)__builtin_amdgcn_readfirstlane(vptr) * kChunk;
-                win_next = load_window(wp_next, lane);
-                if (kb + 2 < kb1) {
-                    vcnt = load_cnt(kb + 2);
-                    vptr = load_ptr(kb + 2);
-                }
-            }
+            for (int j = 0; j < NCW; ++j) cnt_next[j] = __builtin_amdgcn_readlane(meta, j);
+            const int32_t *__restrict__ wp_next =
+                stream + (size_t)(uint32_t)__builtin_amdgcn_readlane(meta, NCW) * kChunk;
+            const int4v win_next = load_window(wp_next, lane);
+            meta = load_meta(clamp_kb(kb + 2));
+
             const char *tile_lane = lds + ((kb - kb0) & 1) * TILE + lane * (R * 4);
             int cc = 0;
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], cnt[j] & 0xffff, cc, win, wp, lane, tile_lane);
-                run_list<R, true>(acc[j], (cnt[j] >> 16) & 0xffff, cc, win, wp, lane, tile_lane);
+                run_list<R, false>(acc[j], cnt[j] & 0xffff, cc, win, wp, tile_lane);
+                run_list<R, true>(acc[j], (cnt[j] >> 16) & 0xffff, cc, win, wp, tile_lane);
             }
-            if (more) {
-                wp = wp_next;
-                win = win_next;
+            wp = wp_next;
+            win = win_next;
 #pragma unroll
-                for (int j = 0; j < NCW; ++j) cnt[j] = cnt_next[j];
-                stage_store((kb + 1 - kb0) & 1);
-            }
+            for (int j = 0; j < NCW; ++j) cnt[j] = cnt_next[j];
+            if (more) stage_store((kb + 1 - kb0) & 1);
             __syncthreads();
         }
     }
@@ -265,17 +268,21 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
 #pragma unroll
         for (int j = 0; j < NCW; ++j)
             *reinterpret_cast<V *>(gbase + (size_t)slice * kSliceFloats + (size_t)j * TM) = acc[j];
-        __threadfence();
+        // Release / acquire through one thread: the barrier orders the workgroup's stores before thread 0's
+        // device-scope fence, and thread 0's fence after the counter update before the workgroup's loads.
         __syncthreads();
         if (threadIdx.x == 0) {
+            __threadfence();
             const int arrived = atomicAdd(&a.counters[group], 1);
             const int last = arrived == a.k_slices - 1;
-            if (last) a.counters[group] = 0;   // ready for the next call
+            if (last) {
+                a.counters[group] = 0;   // ready for the next call
+                __threadfence();
+            }
             last_flag = last;
         }
         __syncthreads();
         if (!last_flag) return;
-        __threadfence();
 #pragma unroll
         for (int j = 0; j < NCW; ++j) {
             V sum = zero_vec<R>();
@@ -344,7 +351,11 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
     const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
+    const bool vec = (l.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    if (vec)
+        hipLaunchKernelGGL((k_large<R, NCW, true>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_large<R, NCW, false>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
