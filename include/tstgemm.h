@@ -4,7 +4,8 @@
  * C ABI of libtstgemm.so.  Plain pointers and sizes only; every pointer argument says
  * whether it is HOST or DEVICE memory.  All functions return 0 (TSTGEMM_OK) or a negative
  * TSTGEMM_E* code; tcsc_strerror() turns a code into text.  No function throws, aborts or
- * prints.  The library keeps no global state besides what a handle owns.
+ * prints.  Besides what a handle owns the library keeps one piece of global state, the tuning
+ * overrides of tstgemm_set_tuning().
  *
  * The operation is Eq. 1 of the paper (Sec. 2): X is dense fp32 (M x K, row-major), W is a
  * K x N matrix with entries in {-1, 0, +1}, b (N) is added to every row of the product,
@@ -72,30 +73,22 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
  * the four TCSC arrays unchanged (read by the small-M kernel), their K-blocked form (read by
  * the large-M kernel) and a workspace for split-K partial sums.  K-blocking follows the idea
- * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block rows so
- * that all X entries one block touches fit in the LDS, and every column's lists are cut at the
- * block borders; as in the paper's blocked format the blocks are stored block after block.
+ * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block = 64 rows
+ * so that all X entries one block touches fit in the LDS, every column's two lists are cut at
+ * the block borders, and the pieces are stored block after block.  A piece holds at most 64
+ * distinct rows of one block, so it is stored as a 64-bit set: bit r of the word stands for
+ * row kb*64 + r.  The kernel turns the set back into row numbers with find-first-set.
  *
- *   seg_count  int32  [n_kblocks][n_pad]  low 16 bits: number of +1 rows of column n inside
- *                                         K-block kb, high 16 bits: number of -1 rows
- *   seg_ptr    uint32 [n_kblocks][n_pad]  where the lists of (kb, n) start in `stream`, in units
- *                                         of `chunk` int32 slots
- *   stream     int32  [stream_len]        K-block after K-block, inside a block column after
- *                                         column: the +1 rows of (kb, n) as block-local row
- *                                         numbers (row - kb*k_block), then the -1 rows, each list
- *                                         stored in chunks of `chunk` slots.  Full chunks come
- *                                         first.  A last partial chunk with r entries (binary
- *                                         r = 4a+2b+c) keeps 4a entries in slots 0..3, 2b in slots
- *                                         4..5, c in slot 6; unused slots hold 0 and are never
- *                                         used by the kernel.
- *   workspace  bytes  [workspace_bytes]   split-K partial sums and arrival counters of tstgemm()
- * n_pad = N rounded up to a multiple of 64; columns >= N have empty lists.
+ *   masks      uint64 [n_kblocks][n_pad][2]   [kb][n][0]: the +1 rows of column n inside K-block
+ *                                             kb, [kb][n][1]: the -1 rows
+ *   workspace  bytes  [workspace_bytes]       split-K partial sums and arrival counters of tstgemm()
+ * n_pad = N rounded up to a multiple of 64; columns >= N have empty sets.
  */
 typedef struct tcsc_layout {
-    int32_t K, N, n_pad, k_block, n_kblocks, chunk;
-    int64_t nnz_pos, nnz_neg, stream_len;
+    int32_t K, N, n_pad, k_block, n_kblocks, reserved;
+    int64_t nnz_pos, nnz_neg;
     size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
-    size_t off_seg_count, off_seg_ptr, off_stream, off_workspace, workspace_bytes, total_bytes;
+    size_t off_masks, off_workspace, workspace_bytes, total_bytes;
 } tcsc_layout_t;
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);

@@ -11,21 +11,6 @@ namespace {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// Padded stream length of one column: every (K-block, sign) list rounded up to whole chunks.
-int64_t column_stream_len(const int32_t *rows_p, int np, const int32_t *rows_n, int nn, int n_kblocks)
-{
-    int64_t len = 0;
-    int ip = 0, in = 0;
-    for (int kb = 0; kb < n_kblocks; ++kb) {
-        const int64_t hi = (int64_t)(kb + 1) * tst::kKBlock;
-        int cp = 0, cn = 0;
-        while (ip < np && rows_p[ip] < hi) { ++ip; ++cp; }
-        while (in < nn && rows_n[in] < hi) { ++in; ++cn; }
-        len += tst::pad_chunk(cp) + tst::pad_chunk(cn);
-    }
-    return len;
-}
-
 void compute_layout(tcsc *t)
 {
     tcsc_layout_t &l = t->layout;
@@ -34,17 +19,9 @@ void compute_layout(tcsc *t)
     l.n_pad = (t->N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
     l.k_block = tst::kKBlock;
     l.n_kblocks = (t->K + tst::kKBlock - 1) / tst::kKBlock;
-    l.chunk = tst::kChunk;
+    l.reserved = 0;
     l.nnz_pos = (int64_t)t->row_index_pos.size();
     l.nnz_neg = (int64_t)t->row_index_neg.size();
-    int64_t len = 0;
-    for (int n = 0; n < t->N; ++n) {
-        const int32_t p0 = t->col_start_pos[n], p1 = t->col_start_pos[n + 1];
-        const int32_t q0 = t->col_start_neg[n], q1 = t->col_start_neg[n + 1];
-        len += column_stream_len(t->row_index_pos.data() + p0, p1 - p0, t->row_index_neg.data() + q0, q1 - q0,
-                                 l.n_kblocks);
-    }
-    l.stream_len = len;
     size_t off = 0;
     auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     l.off_col_start_pos = place(sizeof(int32_t) * (size_t)(t->N + 1));
@@ -52,9 +29,7 @@ void compute_layout(tcsc *t)
     // + 4 entries of slack: the small-M kernel reads the lists in aligned groups of four
     l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + 4));
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + 4));
-    l.off_seg_count = place(sizeof(int32_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
-    l.off_seg_ptr = place(sizeof(uint32_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
-    l.off_stream = place(sizeof(int32_t) * (size_t)(len + tst::kStreamSlack));
+    l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
     l.off_workspace = place(tst::kWorkspaceBytes);
     l.workspace_bytes = tst::kWorkspaceBytes;
     l.total_bytes = off;

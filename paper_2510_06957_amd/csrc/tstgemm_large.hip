@@ -5,27 +5,28 @@
 // multiplications.  The mapping to the machine is this library's own:
 //
 //   * one lane owns R consecutive rows of X (R = 1, 2 or 4), a wavefront therefore owns a
-//     tile of TM = 64 R rows, and walks the index lists of its columns with the index held
-//     in a scalar register: one index serves all TM rows (the paper's "vertical" SIMD scheme
-//     and its M-unrolling, Sec. 3, carried to 64 lanes);
+//     tile of TM = 64 R rows, and walks the index lists of its columns with a wave-uniform
+//     index: one index serves all TM rows (the paper's "vertical" SIMD scheme and its
+//     M-unrolling, Sec. 3, carried to 64 lanes);
 //   * K is cut into blocks of 64 (the paper's blocking idea, Sec. 3 "Blocking"); the
 //     workgroup keeps the X tile of the current block transposed in the LDS, tile[k][row], so
 //     the gather of one index is a single conflict-free ds_read (b32/b64/b128) per lane;
-//   * the next block's tile is fetched from global memory into registers while the current one
-//     is consumed, and written to the second LDS buffer afterwards (one barrier per block);
+//   * gathers are issued eight at a time and added after one wait; the latency of a group is
+//     covered by the other wavefronts (the kernel is built for 8 wavefronts per SIMD: at most
+//     64 VGPRs, two workgroups of 16 wavefronts per compute unit);
+//   * a list piece (one column, one K-block, one sign) arrives as a 64-bit row set; the scalar
+//     unit turns it into row numbers with find-first-set / clear-bit, so an index costs two
+//     SALU instructions and neither VALU work, LDS traffic nor memory latency.  The sets of
+//     a wavefront's columns for the next K-block are fetched one K-block ahead with one vector
+//     load and moved to scalar registers with a few v_readlane at the block border;
+//   * the X tile itself is not prefetched: two workgroups share a compute unit, one computes
+//     while the other exchanges its tile between two barriers;
 //   * accumulators stay in VGPRs over all K-blocks of the workgroup's K slice; the bias add and
 //     the store are fused;
 //   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
 //     8 slices handled by different workgroups; each writes its partial sums to the workspace,
 //     and the workgroup that arrives last adds the slices in slice order, adds the bias and
 //     stores Y -- a fixed summation order, so results do not depend on timing.
-//
-// Index lists come from the K-blocked stream written by the re-blocking pass: per K-block and
-// column a +1 list and a -1 list in 8-slot chunks.  The lists of a wavefront's columns are
-// contiguous, so the wavefront fetches them as one 1 KiB window (16 bytes per lane, one vector
-// load) a whole K-block ahead and then broadcasts one index at a time out of the window into a
-// scalar register (v_readlane): no memory latency sits between two gathers.  The list lengths
-// and the window position travel the same way, two K-blocks ahead.
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -52,16 +53,31 @@ template <int R> __device__ __forceinline__ typename RowVec<R>::type zero_vec()
     if constexpr (R == 1) return 0.f; else return typename RowVec<R>::type(0.f);
 }
 
-// acc (+/-)= tile[idx[i]][rows of this lane], i < COUNT.  All gathers are issued before the first addition so that
-// COUNT LDS reads are in flight at once.
+typedef unsigned long long u64;
+
+// Smallest member of a non-empty row set, removed from the set: two SALU instructions (find-first-set, clear).
+__device__ __forceinline__ int pop_lowest(u64 &set)
+{
+    const int k = __builtin_ctzll(set);
+    set &= set - 1;
+    return k;
+}
+
+template <int R> __device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile_lane, int k)
+{
+    return *reinterpret_cast<const typename RowVec<R>::type *>(tile_lane + k * (64 * R * 4));
+}
+
+// acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it; the set has at
+// least COUNT members).  All gathers are issued before the first addition, so COUNT LDS reads are in flight at once;
+// with 8 wavefronts per SIMD the other wavefronts keep the LDS busy while this one adds.
 template <int R, bool NEG, int COUNT>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile_lane, const int (&idx)[COUNT])
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile_lane, u64 &set)
 {
     typedef typename RowVec<R>::type V;
     V v[COUNT];
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = *reinterpret_cast<const V *>(tile_lane + idx[i] * (64 * R * 4));
+    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile_lane, pop_lowest(set));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
@@ -69,70 +85,24 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char
     }
 }
 
-constexpr int kWindowChunks = 32;                       // chunks per window: 64 lanes x 4 slots
-
-// The 1 KiB of index stream starting at wp, four consecutive slots per lane.
-__device__ __forceinline__ int4v load_window(const int32_t *wp, int lane)
-{
-    return *reinterpret_cast<const int4v *>(wp + 4 * lane);
-}
-
-// The eight slots of chunk cc of the window: slots 0..3 sit in lane 2*cc, slots 4..7 in lane 2*cc+1.  Chunks behind
-// the window (a wavefront whose lists of one K-block exceed 1 KiB: rare) are read straight from the stream with a
-// scalar load.  cc and wp are wave-uniform.
-__device__ __forceinline__ void chunk_slots(int (&idx)[kChunk], const int4v &win, const int32_t *__restrict__ wp, int cc)
-{
-    if (__builtin_expect(cc < kWindowChunks, 1)) {
-        const int l0 = 2 * cc, l1 = l0 + 1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            idx[i] = __builtin_amdgcn_readlane(win[i], l0);
-            idx[4 + i] = __builtin_amdgcn_readlane(win[i], l1);
-        }
-    } else {
-        const int32_t *p = wp + (size_t)cc * kChunk;
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) idx[i] = p[i];
-    }
-}
-
-// One list of n entries starting at chunk `cc` of the window `win` (which starts at wp in the stream); on return cc
-// is the chunk behind the list.  n and cc are wave-uniform.
+// One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
+// in groups of 8 and a remainder of 4 + 2 + 1.  The set is wave-uniform.
 template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, int n, int &cc, const int4v &win,
-                                         const int32_t *__restrict__ wp, const char *tile_lane)
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile_lane)
 {
-    while (n >= kChunk) {
-        int idx[kChunk];
-        chunk_slots(idx, win, wp, cc);
-        gather<R, NEG, kChunk>(acc, tile_lane, idx);
-        n -= kChunk;
-        ++cc;
+    int n = (int)__popcll(set);
+    while (n >= 8) {
+        gather<R, NEG, 8>(acc, tile_lane, set);
+        n -= 8;
     }
-    if (n > 0) {   // partial chunk: 4 entries in slots 0..3 if n&4, 2 in slots 4..5 if n&2, 1 in slot 6 if n&1
-        int idx[kChunk];
-        chunk_slots(idx, win, wp, cc);
-        if (n & 4) {
-            const int four[4] = {idx[0], idx[1], idx[2], idx[3]};
-            gather<R, NEG, 4>(acc, tile_lane, four);
-        }
-        if (n & 2) {
-            const int two[2] = {idx[4], idx[5]};
-            gather<R, NEG, 2>(acc, tile_lane, two);
-        }
-        if (n & 1) {
-            const int one[1] = {idx[6]};
-            gather<R, NEG, 1>(acc, tile_lane, one);
-        }
-        ++cc;
-    }
+    if (n & 4) gather<R, NEG, 4>(acc, tile_lane, set);
+    if (n & 2) gather<R, NEG, 2>(acc, tile_lane, set);
+    if (n & 1) gather<R, NEG, 1>(acc, tile_lane, set);
 }
 
 struct LargeArgs {
     const float *X;
-    const int32_t *seg_count;
-    const uint32_t *seg_ptr;
-    const int32_t *stream;
+    const unsigned long long *masks;
     const float *b;
     float *Y;
     float *partials;
@@ -143,21 +113,19 @@ struct LargeArgs {
 // R rows per lane, NCW columns per wavefront; VEC: X rows are 16-byte aligned and K is a multiple of 4, so X is
 // staged with 16-byte loads (otherwise element by element).
 template <int R, int NCW, bool VEC>
-__global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
+__global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
     constexpr int TM = 64 * R;            // rows of X per workgroup tile
     constexpr int RB = TM * 4;            // bytes of one tile row (one k, TM rows)
-    constexpr int TILE = kKBlock * RB;    // bytes of one buffer
+    constexpr int TILE = kKBlock * RB;    // bytes of the tile
     constexpr int NT = NW * 64;
     constexpr int CPT = TM * (kKBlock / 4) / NT;   // 16-byte pieces of X each thread stages per K-block
     static_assert(CPT >= 1 && CPT * NT == TM * (kKBlock / 4), "staging must tile the block exactly");
-
-    __shared__ __attribute__((aligned(16))) char lds[2 * TILE];
+    __shared__ __attribute__((aligned(16))) char lds[TILE];
     __shared__ int last_flag;
 
     const float *__restrict__ X = a.X;
-    const int32_t *__restrict__ stream = a.stream;
     const int M = a.M, K = a.K, N = a.N, n_pad = a.n_pad;
 
     const int lane = threadIdx.x & 63;
@@ -175,11 +143,11 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
     const int gm = m0 + srow;
     const bool row_ok = gm < M;
     const float *xrow = X + (size_t)(row_ok ? gm : M - 1) * K;
-    float4v st[CPT];
 
-    // All loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are
-    // zeroed afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
-    auto stage_load = [&](int kb) {
+    // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
+    // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
+    auto stage_tile = [&](int kb) {
+        float4v st[CPT];
         const int k0 = kb * kKBlock + sseg * (4 * CPT);
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
@@ -198,9 +166,7 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
             }
             st[i] = v;
         }
-    };
-    auto stage_store = [&](int buf) {
-        char *base = lds + buf * TILE + (sseg * (4 * CPT)) * RB + srow * 4;
+        char *base = lds + (sseg * (4 * CPT)) * RB + srow * 4;
 #pragma unroll
         for (int i = 0; i < CPT; ++i)
 #pragma unroll
@@ -213,50 +179,33 @@ __global__ void __launch_bounds__(NW * 64) k_large(const LargeArgs a)
     for (int j = 0; j < NCW; ++j) acc[j] = zero_vec<R>();
 
     if (kb0 < kb1) {
-        // List lengths and window position of (kb, c0 .. c0+NCW-1) come through ONE vector load: lane j < NCW reads
-        // the packed counts of column c0+j, lane NCW the position of the first chunk (the pattern repeats every
-        // 2*NCW lanes).  A scalar load would share its wait counter with the LDS gathers.
-        const int32_t *meta_base = (lane & NCW) ? reinterpret_cast<const int32_t *>(a.seg_ptr) + c0
-                                                : a.seg_count + c0 + (lane & (NCW - 1));
-        auto load_meta = [&](int kb) { return meta_base[(size_t)kb * n_pad]; };
-        auto clamp_kb = [&](int kb) { return kb < kb1 ? kb : kb1 - 1; };
-        int meta = load_meta(kb0);
-        stage_load(kb0);
-        int cnt[NCW];
-#pragma unroll
-        for (int j = 0; j < NCW; ++j) cnt[j] = __builtin_amdgcn_readlane(meta, j);
-        const int32_t *__restrict__ wp = stream + (size_t)(uint32_t)__builtin_amdgcn_readlane(meta, NCW) * kChunk;
-        int4v win = load_window(wp, lane);
-        meta = load_meta(clamp_kb(kb0 + 1));
-        stage_store(0);
-        __syncthreads();
+        // Row sets of (kb, c0 .. c0+NCW-1): 4*NCW consecutive dwords (column j: +1 set low/high, -1 set low/high),
+        // fetched by lanes 0 .. 4*NCW-1 of one vector load a K-block ahead.  A scalar load would share its wait
+        // counter with the LDS reads and stall the pipeline.
+        const uint32_t *set_words = reinterpret_cast<const uint32_t *>(a.masks) + (size_t)c0 * 4 + (lane & (4 * NCW - 1));
+        auto load_sets = [&](int kb) { return (int)set_words[(size_t)kb * n_pad * 4]; };
+        int sets_next = load_sets(kb0);
+        const char *tile_lane = lds + lane * (R * 4);
 
         for (int kb = kb0; kb < kb1; ++kb) {
-            // requests for the next K-block (tile, window) and the one after it (list lengths, window position);
-            // behind the last block they repeat the last one and are not used
-            const bool more = kb + 1 < kb1;
-            stage_load(clamp_kb(kb + 1));
-            int cnt_next[NCW];
+            // Exchange the tile between two barriers; the other workgroup on this compute unit computes meanwhile.
+            if (kb > kb0) __syncthreads();
+            stage_tile(kb);
+            __syncthreads();
+            auto set_of = [&](int i) {
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(sets_next, 2 * i);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(sets_next, 2 * i + 1);
+                return ((u64)hi << 32) | lo;
+            };
+            u64 sets[2 * NCW];
 #pragma unroll
-            for (int j = 0; j < NCW; ++j) cnt_next[j] = __builtin_amdgcn_readlane(meta, j);
-            const int32_t *__restrict__ wp_next =
-                stream + (size_t)(uint32_t)__builtin_amdgcn_readlane(meta, NCW) * kChunk;
-            const int4v win_next = load_window(wp_next, lane);
-            meta = load_meta(clamp_kb(kb + 2));
-
-            const char *tile_lane = lds + ((kb - kb0) & 1) * TILE + lane * (R * 4);
-            int cc = 0;
+            for (int i = 0; i < 2 * NCW; ++i) sets[i] = set_of(i);
+            sets_next = load_sets(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], cnt[j] & 0xffff, cc, win, wp, tile_lane);
-                run_list<R, true>(acc[j], (cnt[j] >> 16) & 0xffff, cc, win, wp, tile_lane);
+                run_list<R, false>(acc[j], sets[2 * j], tile_lane);
+                run_list<R, true>(acc[j], sets[2 * j + 1], tile_lane);
             }
-            wp = wp_next;
-            win = win_next;
-#pragma unroll
-            for (int j = 0; j < NCW; ++j) cnt[j] = cnt_next[j];
-            if (more) stage_store((kb + 1 - kb0) & 1);
-            __syncthreads();
         }
     }
 
@@ -339,7 +288,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
     const DeviceTcsc d = device_view(t);
     constexpr int TM = 64 * R;
     LargeArgs a;
-    a.X = X; a.seg_count = d.seg_count; a.seg_ptr = d.seg_ptr; a.stream = d.stream; a.b = b; a.Y = Y;
+    a.X = X; a.masks = d.masks; a.b = b; a.Y = Y;
     a.partials = d.partials; a.counters = d.counters;
     a.M = M; a.K = l.K; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
@@ -364,13 +313,13 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
 template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
-    const int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
+    const int ncw = g_cols_per_wave ? g_cols_per_wave : 2;
     const long long m_tiles = (M + 64 * R - 1) / (64 * R);
     const long long groups = m_tiles * (l.n_pad / (NW * ncw));
     int k_slices = g_k_slices;
     if (k_slices == 0) {
-        const int cus = compute_units();
-        k_slices = groups >= cus ? 1 : (int)((cus + groups - 1) / groups);
+        const int slots = 2 * compute_units();   // two workgroups per compute unit
+        k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
         if (k_slices > 8) k_slices = 8;
     }
     if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;

@@ -40,7 +40,7 @@ def assert_exact(Y, Yd, what=""):
 
 
 def decode_device_form(t):
-    """Dense W rebuilt from the K-blocked device streams (seg_count, col_ptr, stream), plus the four
+    """Dense W rebuilt from the K-blocked device form (64-bit row sets), plus the four
     canonical arrays as they sit in the device buffer.  Written against the layout documented in
     include/tstgemm.h, independent of the library's own code."""
     import torch
@@ -54,39 +54,15 @@ def decode_device_form(t):
 
     canon = (view(lay.off_col_start_pos, lay.N + 1, np.int32), view(lay.off_col_start_neg, lay.N + 1, np.int32),
              view(lay.off_row_index_pos, lay.nnz_pos, np.int32), view(lay.off_row_index_neg, lay.nnz_neg, np.int32))
-    seg = view(lay.off_seg_count, lay.n_kblocks * lay.n_pad, np.int32).reshape(lay.n_kblocks, lay.n_pad)
-    seg_ptr = view(lay.off_seg_ptr, lay.n_kblocks * lay.n_pad, np.uint32).reshape(lay.n_kblocks, lay.n_pad)
-    stream = view(lay.off_stream, lay.stream_len, np.int32)
-    W = np.zeros((lay.K, lay.N), np.int8)
-    C = lay.chunk
-
-    def read_list(pos, count):
-        full = count // C * C
-        vals = list(stream[pos:pos + full])
-        r = count - full
-        if r:
-            ch = stream[pos + full:pos + full + C]
-            if r & 4:
-                vals += list(ch[0:4])
-            if r & 2:
-                vals += list(ch[4:6])
-            if r & 1:
-                vals.append(ch[6])
-        return np.array(vals, dtype=np.int64), pos + (count + C - 1) // C * C
-
-    pos = 0   # lists are stored K-block after K-block, column after column, without gaps
-    for kb in range(lay.n_kblocks):
-        for n in range(lay.n_pad):
-            c = int(seg[kb, n])
-            cp, cn = c & 0xffff, (c >> 16) & 0xffff
-            assert int(seg_ptr[kb, n]) * C == pos
-            if n >= lay.N:
-                assert c == 0
-                continue
-            for count, sign in ((cp, 1), (cn, -1)):
-                rows, pos = read_list(pos, count)
-                assert rows.size == 0 or (rows.min() >= 0 and rows.max() < lay.k_block and np.all(np.diff(rows) > 0))
-                assert np.all(W[kb * lay.k_block + rows, n] == 0)
-                W[kb * lay.k_block + rows, n] = sign
-    assert pos == lay.stream_len
+    masks = view(lay.off_masks, lay.n_kblocks * lay.n_pad * 2, np.uint64).reshape(lay.n_kblocks, lay.n_pad, 2)
+    assert lay.k_block == 64
+    assert not masks[:, lay.N:, :].any()                      # padding columns are empty
+    assert not (masks[:, :, 0] & masks[:, :, 1]).any()        # a row is +1 or -1, never both
+    W = np.zeros((lay.n_kblocks * 64, lay.N), np.int8)
+    for r in range(64):
+        bit = np.uint64(1) << np.uint64(r)
+        W[r::64][(masks[:, :lay.N, 0] & bit) != 0] = 1
+        W[r::64][(masks[:, :lay.N, 1] & bit) != 0] = -1
+    assert not W[lay.K:].any()                                # no row at or beyond K
+    W = W[:lay.K]
     return W, canon

@@ -108,18 +108,12 @@ def test_layout_bookkeeping():
     W, _, _ = si.make_inputs(1, 513, 65, 0.5, "uniform", seed=5)
     t = tg.tcsc_build(W)
     lay = tg.tcsc_layout(t)
-    assert (lay.K, lay.N, lay.k_block, lay.chunk) == (513, 65, 64, 8)
+    assert (lay.K, lay.N, lay.k_block) == (513, 65, 64)
     assert lay.n_pad % 64 == 0 and lay.n_pad >= 65 and lay.n_kblocks == -(-513 // 64)
-    # stream length recomputed from the dense matrix: every (column, K-block, sign) list padded to whole chunks
-    expect = 0
-    for kb in range(lay.n_kblocks):
-        blk = W[kb * 64:(kb + 1) * 64]
-        for cnt in ((blk == 1).sum(axis=0), (blk == -1).sum(axis=0)):
-            expect += int((-(-cnt // 8) * 8).sum())
-    assert lay.stream_len == expect
+    assert (lay.nnz_pos, lay.nnz_neg) == (int((W == 1).sum()), int((W == -1).sum()))
     offs = [lay.off_col_start_pos, lay.off_col_start_neg, lay.off_row_index_pos, lay.off_row_index_neg,
-            lay.off_seg_count, lay.off_seg_ptr, lay.off_stream, lay.off_workspace, lay.total_bytes]
+            lay.off_masks, lay.off_workspace, lay.total_bytes]
     assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
     assert lay.total_bytes == tg.tcsc_device_bytes(t)
-    assert lay.off_workspace - lay.off_stream >= 4 * lay.stream_len
+    assert lay.off_workspace - lay.off_masks >= 16 * lay.n_kblocks * lay.n_pad
     assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
