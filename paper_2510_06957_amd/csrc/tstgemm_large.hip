@@ -55,29 +55,41 @@ template <int R> __device__ __forceinline__ typename RowVec<R>::type zero_vec()
 
 typedef unsigned long long u64;
 
-// Smallest member of a non-empty row set, removed from the set: two SALU instructions (find-first-set, clear).
+// Smallest member of a non-empty row set, removed from the set: two SALU instructions (find-first-set, clear bit).
 __device__ __forceinline__ int pop_lowest(u64 &set)
 {
     const int k = __builtin_ctzll(set);
-    set &= set - 1;
+    asm("s_bitset0_b64 %0, %1" : "+s"(set) : "s"(k));
     return k;
 }
 
-template <int R> __device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile_lane, int k)
+// LDS layout of the X tile.  Row k of the tile holds X[m0 .. m0+TM)[k0 + k], TM = 64 R floats = 16 R groups of
+// 16 bytes.  Group g of row k is stored at group position g ^ (k & GMASK): a lane still finds its rows with one
+// XOR, all lanes of a gather still hit distinct banks (XOR permutes the groups of a row), and the transposing
+// writes of the staging, whose lanes differ in k, spread over all banks instead of piling up on four.
+// swizzle_of(k) is the wave-uniform part of the address: byte offset of row k combined with the XOR term.
+template <int R> __device__ __forceinline__ int swizzle_of(int k)
 {
-    return *reinterpret_cast<const typename RowVec<R>::type *>(tile_lane + k * (64 * R * 4));
+    if constexpr (R == 4) return k * (1024 + 16);                   // rows of 1 KiB, 64 groups: k < 64 moves every group bit
+    else return k * (256 * R) + ((k & 15) << 4);                    // 16 or 32 groups: XOR of the low 4 group bits
+}
+
+// This lane's R rows of tile row k; lane_base is the byte offset of the lane's rows inside an unswizzled row.
+template <int R> __device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int k)
+{
+    return *reinterpret_cast<const typename RowVec<R>::type *>(tile + (swizzle_of<R>(k) ^ lane_base));
 }
 
 // acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it; the set has at
 // least COUNT members).  All gathers are issued before the first addition, so COUNT LDS reads are in flight at once;
 // with 8 wavefronts per SIMD the other wavefronts keep the LDS busy while this one adds.
 template <int R, bool NEG, int COUNT>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile_lane, u64 &set)
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile, int lane_base, u64 &set)
 {
     typedef typename RowVec<R>::type V;
     V v[COUNT];
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile_lane, pop_lowest(set));
+    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile, lane_base, pop_lowest(set));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
@@ -88,16 +100,16 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
 // in groups of 8 and a remainder of 4 + 2 + 1.  The set is wave-uniform.
 template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile_lane)
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile, int lane_base)
 {
     int n = (int)__popcll(set);
     while (n >= 8) {
-        gather<R, NEG, 8>(acc, tile_lane, set);
+        gather<R, NEG, 8>(acc, tile, lane_base, set);
         n -= 8;
     }
-    if (n & 4) gather<R, NEG, 4>(acc, tile_lane, set);
-    if (n & 2) gather<R, NEG, 2>(acc, tile_lane, set);
-    if (n & 1) gather<R, NEG, 1>(acc, tile_lane, set);
+    if (n & 4) gather<R, NEG, 4>(acc, tile, lane_base, set);
+    if (n & 2) gather<R, NEG, 2>(acc, tile, lane_base, set);
+    if (n & 1) gather<R, NEG, 1>(acc, tile, lane_base, set);
 }
 
 struct LargeArgs {
@@ -138,20 +150,22 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
     const int kb0 = min(slice * a.kb_per_slice, a.n_kblocks);
     const int kb1 = min(kb0 + a.kb_per_slice, a.n_kblocks);
 
-    // ---- staging role of this thread: row `srow` of the tile, k-segment `sseg`
-    const int srow = threadIdx.x % TM, sseg = threadIdx.x / TM;
+    // ---- staging role of this thread.  Four neighbouring lanes fetch 64 contiguous bytes of one X row (a
+    // wavefront load touches 16 rows), and a thread owns the 16-byte pieces spiece + 4 i, i < CPT, of tile row srow.
+    const int srow = (threadIdx.x >> 2) % TM;
+    const int spiece = (threadIdx.x & 3) + 4 * CPT * (threadIdx.x / (4 * TM));
     const int gm = m0 + srow;
     const bool row_ok = gm < M;
     const float *xrow = X + (size_t)(row_ok ? gm : M - 1) * K;
+    constexpr int GMASK = R == 4 ? 63 : 15;
 
     // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
     // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
     auto stage_tile = [&](int kb) {
         float4v st[CPT];
-        const int k0 = kb * kKBlock + sseg * (4 * CPT);
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int k = k0 + 4 * i;
+            const int k = kb * kKBlock + 4 * (spiece + 4 * i);
             float4v v;
             if constexpr (VEC) {
                 const bool ok = row_ok && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
@@ -166,11 +180,14 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
             }
             st[i] = v;
         }
-        char *base = lds + (sseg * (4 * CPT)) * RB + srow * 4;
 #pragma unroll
         for (int i = 0; i < CPT; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<float *>(base + (4 * i + j) * RB) = st[i][j];
+            for (int j = 0; j < 4; ++j) {
+                const int k = 4 * (spiece + 4 * i) + j;   // tile row
+                const int group = (srow >> 2) ^ (k & GMASK);
+                *reinterpret_cast<float *>(lds + k * RB + group * 16 + (srow & 3) * 4) = st[i][j];
+            }
     };
 
     // ---- compute role: columns c0 .. c0+NCW-1, rows m0 + R*lane .. + R-1
@@ -185,7 +202,7 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
         const uint32_t *set_words = reinterpret_cast<const uint32_t *>(a.masks) + (size_t)c0 * 4 + (lane & (4 * NCW - 1));
         auto load_sets = [&](int kb) { return (int)set_words[(size_t)kb * n_pad * 4]; };
         int sets_next = load_sets(kb0);
-        const char *tile_lane = lds + lane * (R * 4);
+        const int lane_base = lane * (R * 4);
 
         for (int kb = kb0; kb < kb1; ++kb) {
             // Exchange the tile between two barriers; the other workgroup on this compute unit computes meanwhile.
@@ -203,8 +220,8 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
             sets_next = load_sets(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], sets[2 * j], tile_lane);
-                run_list<R, true>(acc[j], sets[2 * j + 1], tile_lane);
+                run_list<R, false>(acc[j], sets[2 * j], lds, lane_base);
+                run_list<R, true>(acc[j], sets[2 * j + 1], lds, lane_base);
             }
         }
     }
