@@ -120,6 +120,7 @@ struct LargeArgs {
     float *partials;
     int32_t *counters;
     int M, K, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
+    int wg_slots;   // workgroups of one dispatch round: blocks i and i + wg_slots tend to share a compute unit
 };
 
 // R rows per lane, NCW columns per wavefront; VEC: X rows are 16-byte aligned and K is a multiple of 4, so X is
@@ -161,8 +162,8 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
 
     // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
     // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
-    auto stage_tile = [&](int kb) {
-        float4v st[CPT];
+    float4v st[CPT];
+    auto stage_load = [&](int kb) {
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int k = kb * kKBlock + 4 * (spiece + 4 * i);
@@ -180,6 +181,8 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
             }
             st[i] = v;
         }
+    };
+    auto stage_store = [&]() {
 #pragma unroll
         for (int i = 0; i < CPT; ++i)
 #pragma unroll
@@ -204,10 +207,17 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
         int sets_next = load_sets(kb0);
         const int lane_base = lane * (R * 4);
 
+        const int wg_parity = (blockIdx.x / a.wg_slots) & 1;
+        stage_load(kb0);
         for (int kb = kb0; kb < kb1; ++kb) {
+            // The two workgroups that share a compute unit take turns in issue priority, K-block by K-block: the
+            // hardware would otherwise always prefer the older one, which then finishes long before the other.
+            if (((kb - kb0) + wg_parity) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
             // Exchange the tile between two barriers; the other workgroup on this compute unit computes meanwhile.
+            // The loads of the tile were issued when this wavefront finished the previous K-block, so most of
+            // their latency has passed while it waited for the slower wavefronts at the first barrier.
             if (kb > kb0) __syncthreads();
-            stage_tile(kb);
+            stage_store();
             __syncthreads();
             auto set_of = [&](int i) {
                 const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(sets_next, 2 * i);
@@ -223,6 +233,7 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
                 run_list<R, false>(acc[j], sets[2 * j], lds, lane_base);
                 run_list<R, true>(acc[j], sets[2 * j + 1], lds, lane_base);
             }
+            stage_load(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
         }
     }
 
@@ -249,11 +260,20 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
         }
         __syncthreads();
         if (!last_flag) return;
+        // All slices of a column are requested before the first addition (one memory round trip instead of
+        // k_slices); the additions then run in slice order.
+        constexpr int kMaxSlices = 8;
 #pragma unroll
         for (int j = 0; j < NCW; ++j) {
+            V part[kMaxSlices];
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+                part[s] = *reinterpret_cast<const V *>(gbase + (size_t)(s < a.k_slices ? s : 0) * kSliceFloats +
+                                                       (size_t)j * TM);
             V sum = zero_vec<R>();
-            for (int s = 0; s < a.k_slices; ++s)
-                sum += *reinterpret_cast<const V *>(gbase + (size_t)s * kSliceFloats + (size_t)j * TM);
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+                if (s < a.k_slices) sum += part[s];
             acc[j] = sum;
         }
     }
@@ -315,6 +335,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
+    a.wg_slots = compute_units();
     const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool vec = (l.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
