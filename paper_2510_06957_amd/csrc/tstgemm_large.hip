@@ -53,43 +53,50 @@ template <int R> __device__ __forceinline__ typename RowVec<R>::type zero_vec()
     if constexpr (R == 1) return 0.f; else return typename RowVec<R>::type(0.f);
 }
 
-typedef unsigned long long u64;
+// A stage of the kernel covers half a K-block: 32 rows of W, one 32-bit half of a 64-bit row set.
+constexpr int kStageRows = kKBlock / 2;
 
 // Smallest member of a non-empty row set, removed from the set: two SALU instructions (find-first-set, clear bit).
-__device__ __forceinline__ int pop_lowest(u64 &set)
+__device__ __forceinline__ int pop_lowest(uint32_t &set)
 {
-    const int k = __builtin_ctzll(set);
-    asm("s_bitset0_b64 %0, %1" : "+s"(set) : "s"(k));
+    const int k = __builtin_ctz(set);
+    asm("s_bitset0_b32 %0, %1" : "+s"(set) : "s"(k));
     return k;
 }
 
-// LDS layout of the X tile.  Row k of the tile holds X[m0 .. m0+TM)[k0 + k], TM = 64 R floats = 16 R groups of
-// 16 bytes.  Group g of row k is stored at group position g ^ (k & GMASK): a lane still finds its rows with one
-// XOR, all lanes of a gather still hit distinct banks (XOR permutes the groups of a row), and the transposing
-// writes of the staging, whose lanes differ in k, spread over all banks instead of piling up on four.
-// swizzle_of(k) is the wave-uniform part of the address: byte offset of row k combined with the XOR term.
-template <int R> __device__ __forceinline__ int swizzle_of(int k)
+// LDS layout of an X tile: tile row k (one column of X, TM = 64 R consecutive rows of X) starts at k * stride,
+// stride = 4 TM + 16 bytes.  The 16 bytes of padding rotate the banks by four from one tile row to the next, so
+// that the transposing writes of the staging (lanes that differ in k and in the X row) hit 64 different banks,
+// while a gather (all lanes the same k, consecutive X rows) stays contiguous and 16-byte aligned.
+template <int R> constexpr int tile_stride() { return 256 * R + 16; }
+
+// This lane's R rows of tile row k: address = k * stride + lane_base in one VALU instruction (k is wave-uniform).
+template <int R>
+__device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int stride_vgpr, int k)
 {
-    if constexpr (R == 4) return k * (1024 + 16);                   // rows of 1 KiB, 64 groups: k < 64 moves every group bit
-    else return k * (256 * R) + ((k & 15) << 4);                    // 16 or 32 groups: XOR of the low 4 group bits
+    int off;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "s"(k), "v"(stride_vgpr), "v"(lane_base));
+    return *reinterpret_cast<const typename RowVec<R>::type *>(tile + off);
 }
 
-// This lane's R rows of tile row k; lane_base is the byte offset of the lane's rows inside an unswizzled row.
-template <int R> __device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int k)
-{
-    return *reinterpret_cast<const typename RowVec<R>::type *>(tile + (swizzle_of<R>(k) ^ lane_base));
-}
+// What a gather needs besides the row number: the tile, this lane's byte offset inside a tile row (plus the offset of
+// the buffer in use), and the row stride held in a VGPR (the multiply-add takes only one scalar operand).
+struct TileView {
+    const char *tile;
+    int lane_base;
+    int stride_vgpr;
+};
 
 // acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it; the set has at
 // least COUNT members).  All gathers are issued before the first addition, so COUNT LDS reads are in flight at once;
 // with 8 wavefronts per SIMD the other wavefronts keep the LDS busy while this one adds.
 template <int R, bool NEG, int COUNT>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile, int lane_base, u64 &set)
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const TileView &t, uint32_t &set)
 {
     typedef typename RowVec<R>::type V;
     V v[COUNT];
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile, lane_base, pop_lowest(set));
+    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(t.tile, t.lane_base, t.stride_vgpr, pop_lowest(set));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
@@ -100,16 +107,16 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
 // in groups of 8 and a remainder of 4 + 2 + 1.  The set is wave-uniform.
 template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile, int lane_base)
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, uint32_t set, const TileView &t)
 {
-    int n = (int)__popcll(set);
+    int n = __builtin_popcount(set);
     while (n >= 8) {
-        gather<R, NEG, 8>(acc, tile, lane_base, set);
+        gather<R, NEG, 8>(acc, t, set);
         n -= 8;
     }
-    if (n & 4) gather<R, NEG, 4>(acc, tile, lane_base, set);
-    if (n & 2) gather<R, NEG, 2>(acc, tile, lane_base, set);
-    if (n & 1) gather<R, NEG, 1>(acc, tile, lane_base, set);
+    if (n & 4) gather<R, NEG, 4>(acc, t, set);
+    if (n & 2) gather<R, NEG, 2>(acc, t, set);
+    if (n & 1) gather<R, NEG, 1>(acc, t, set);
 }
 
 struct LargeArgs {
@@ -130,12 +137,13 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
     constexpr int TM = 64 * R;            // rows of X per workgroup tile
-    constexpr int RB = TM * 4;            // bytes of one tile row (one k, TM rows)
-    constexpr int TILE = kKBlock * RB;    // bytes of the tile
+    constexpr int RB = tile_stride<R>();         // bytes from one tile row (one k, TM rows) to the next
+    constexpr int TILE = kStageRows * RB;        // bytes of one buffer
     constexpr int NT = NW * 64;
-    constexpr int CPT = TM * (kKBlock / 4) / NT;   // 16-byte pieces of X each thread stages per K-block
-    static_assert(CPT >= 1 && CPT * NT == TM * (kKBlock / 4), "staging must tile the block exactly");
-    __shared__ __attribute__((aligned(16))) char lds[TILE];
+    constexpr int PIECES = kStageRows / 4;       // 16-byte pieces of an X row per stage
+    constexpr int ROWS_PER_PASS = NT / PIECES;   // X rows the workgroup fetches with one load per thread
+    constexpr int CPT = (TM + ROWS_PER_PASS - 1) / ROWS_PER_PASS;   // loads per thread and stage
+    __shared__ __attribute__((aligned(16))) char lds[2 * TILE];
     __shared__ int last_flag;
 
     const float *__restrict__ X = a.X;
@@ -151,22 +159,25 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
     const int kb0 = min(slice * a.kb_per_slice, a.n_kblocks);
     const int kb1 = min(kb0 + a.kb_per_slice, a.n_kblocks);
 
-    // ---- staging role of this thread.  Four neighbouring lanes fetch 64 contiguous bytes of one X row (a
-    // wavefront load touches 16 rows), and a thread owns the 16-byte pieces spiece + 4 i, i < CPT, of tile row srow.
-    const int srow = (threadIdx.x >> 2) % TM;
-    const int spiece = (threadIdx.x & 3) + 4 * CPT * (threadIdx.x / (4 * TM));
-    const int gm = m0 + srow;
-    const bool row_ok = gm < M;
-    const float *xrow = X + (size_t)(row_ok ? gm : M - 1) * K;
-    constexpr int GMASK = R == 4 ? 63 : 15;
+    // ---- staging role of this thread.  A stage needs 32 consecutive floats (8 pieces of 16 bytes) of every X row
+    // of the tile.  Four neighbouring lanes fetch 64 contiguous bytes of one row, so a wavefront load touches 16
+    // rows; thread t owns piece (t & 3) + 4 * ((t >> 2) / ROWS...) -- in short: row srow + i * ROWS_PER_PASS, piece
+    // spiece, for i < CPT.
+    const int spiece = (threadIdx.x & 3) + 4 * ((threadIdx.x >> 2) / ROWS_PER_PASS % (PIECES / 4));
+    const int srow = (threadIdx.x >> 2) % ROWS_PER_PASS + ROWS_PER_PASS * ((threadIdx.x >> 2) / ROWS_PER_PASS / (PIECES / 4));
+    static_assert(PIECES == 8 && NT % PIECES == 0, "staging layout");
+    float4v st[CPT];
 
     // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
     // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
-    float4v st[CPT];
-    auto stage_load = [&](int kb) {
+    auto stage_load = [&](int stage) {
+        const int k = stage * kStageRows + 4 * spiece;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int k = kb * kKBlock + 4 * (spiece + 4 * i);
+            const int row = srow + i * (NT / 4 / (PIECES / 4));
+            const int gm = m0 + row;
+            const bool row_ok = row < TM && gm < M;
+            const float *xrow = X + (size_t)(gm < M ? gm : M - 1) * K;
             float4v v;
             if constexpr (VEC) {
                 const bool ok = row_ok && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
@@ -182,15 +193,16 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
             st[i] = v;
         }
     };
-    auto stage_store = [&]() {
+    auto stage_store = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < CPT; ++i)
+        for (int i = 0; i < CPT; ++i) {
+            const int row = srow + i * (NT / 4 / (PIECES / 4));
+            if (row < TM) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = 4 * (spiece + 4 * i) + j;   // tile row
-                const int group = (srow >> 2) ^ (k & GMASK);
-                *reinterpret_cast<float *>(lds + k * RB + group * 16 + (srow & 3) * 4) = st[i][j];
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<float *>(lds + buf * TILE + (4 * spiece + j) * RB + row * 4) = st[i][j];
             }
+        }
     };
 
     // ---- compute role: columns c0 .. c0+NCW-1, rows m0 + R*lane .. + R-1
@@ -199,41 +211,46 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
     for (int j = 0; j < NCW; ++j) acc[j] = zero_vec<R>();
 
     if (kb0 < kb1) {
-        // Row sets of (kb, c0 .. c0+NCW-1): 4*NCW consecutive dwords (column j: +1 set low/high, -1 set low/high),
-        // fetched by lanes 0 .. 4*NCW-1 of one vector load a K-block ahead.  A scalar load would share its wait
-        // counter with the LDS reads and stall the pipeline.
+        // Row sets of (kb, c0 .. c0+NCW-1): 4*NCW consecutive dwords (column j: +1 set low/high half, -1 set low/high
+        // half), fetched by lanes 0 .. 4*NCW-1 of one vector load a K-block ahead.  A scalar load would share its
+        // wait counter with the LDS reads.
         const uint32_t *set_words = reinterpret_cast<const uint32_t *>(a.masks) + (size_t)c0 * 4 + (lane & (4 * NCW - 1));
         auto load_sets = [&](int kb) { return (int)set_words[(size_t)kb * n_pad * 4]; };
-        int sets_next = load_sets(kb0);
+        int sets_cur = load_sets(kb0), sets_next = sets_cur;
+        TileView view;
+        view.tile = lds;
+        view.stride_vgpr = RB;
         const int lane_base = lane * (R * 4);
-
         const int wg_parity = (blockIdx.x / a.wg_slots) & 1;
-        stage_load(kb0);
-        for (int kb = kb0; kb < kb1; ++kb) {
-            // The two workgroups that share a compute unit take turns in issue priority, K-block by K-block: the
+
+        // Stages: two per K-block (its low and its high 32 rows), double-buffered in the LDS.  While a stage is
+        // computed the X tile of the next one sits in registers (requested at the start of the stage) and is written
+        // to the other buffer at the end; one barrier per stage.
+        const int s0 = 2 * kb0, s1 = 2 * kb1;
+        stage_load(s0);
+        stage_store(0);
+        __syncthreads();
+        for (int stage = s0; stage < s1; ++stage) {
+            const int half = stage & 1;
+            // The two workgroups that share a compute unit take turns in issue priority, stage by stage: the
             // hardware would otherwise always prefer the older one, which then finishes long before the other.
-            if (((kb - kb0) + wg_parity) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-            // Exchange the tile between two barriers; the other workgroup on this compute unit computes meanwhile.
-            // The loads of the tile were issued when this wavefront finished the previous K-block, so most of
-            // their latency has passed while it waited for the slower wavefronts at the first barrier.
-            if (kb > kb0) __syncthreads();
-            stage_store();
-            __syncthreads();
-            auto set_of = [&](int i) {
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(sets_next, 2 * i);
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(sets_next, 2 * i + 1);
-                return ((u64)hi << 32) | lo;
-            };
-            u64 sets[2 * NCW];
-#pragma unroll
-            for (int i = 0; i < 2 * NCW; ++i) sets[i] = set_of(i);
-            sets_next = load_sets(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
+            if ((((stage - s0) >> 1) + wg_parity) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+            stage_load(stage + 1 < s1 ? stage + 1 : stage);   // behind the last stage: repeated, not used
+            if (half == 0) {
+                sets_cur = sets_next;
+                const int kb = stage >> 1;
+                sets_next = load_sets(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
+            }
+            view.lane_base = lane_base + ((stage - s0) & 1) * TILE;
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], sets[2 * j], lds, lane_base);
-                run_list<R, true>(acc[j], sets[2 * j + 1], lds, lane_base);
+                const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane(sets_cur, 4 * j + half);
+                const uint32_t neg = (uint32_t)__builtin_amdgcn_readlane(sets_cur, 4 * j + 2 + half);
+                run_list<R, false>(acc[j], pos, view);
+                run_list<R, true>(acc[j], neg, view);
             }
-            stage_load(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
+            if (stage + 1 < s1) stage_store(((stage - s0) & 1) ^ 1);
+            __syncthreads();
         }
     }
 
