@@ -368,7 +368,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
 template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
-    const int ncw = g_cols_per_wave ? g_cols_per_wave : 2;
+    const int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
     const long long m_tiles = (M + 64 * R - 1) / (64 * R);
     const long long groups = m_tiles * (l.n_pad / (NW * ncw));
     int k_slices = g_k_slices;
