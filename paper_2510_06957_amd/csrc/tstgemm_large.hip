@@ -170,24 +170,31 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
 
     // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
     // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
+    // Byte offsets of this thread's X rows from the first row of the tile, as 32-bit values next to a wave-uniform
+    // 64-bit base (rows beyond M point at the last valid row and are zeroed after the load).
+    const char *xtile = reinterpret_cast<const char *>(X + (size_t)m0 * K);
+    uint32_t xoff[CPT];
+    bool xok[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int row = srow + i * (NT / 4 / (PIECES / 4));
+        xok[i] = row < TM && m0 + row < M;
+        xoff[i] = (uint32_t)(min(row, M - 1 - m0)) * (uint32_t)K * 4u;
+    }
     auto stage_load = [&](int stage) {
         const int k = stage * kStageRows + 4 * spiece;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int row = srow + i * (NT / 4 / (PIECES / 4));
-            const int gm = m0 + row;
-            const bool row_ok = row < TM && gm < M;
-            const float *xrow = X + (size_t)(gm < M ? gm : M - 1) * K;
             float4v v;
             if constexpr (VEC) {
-                const bool ok = row_ok && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
-                v = *reinterpret_cast<const float4v *>(xrow + (k < K ? k : 0));
+                const bool ok = xok[i] && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
+                v = *reinterpret_cast<const float4v *>(xtile + (xoff[i] + (uint32_t)(k < K ? k : 0) * 4u));
                 if (!ok) v = float4v{0.f, 0.f, 0.f, 0.f};
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float x = xrow[k + j < K ? k + j : 0];
-                    v[j] = (row_ok && k + j < K) ? x : 0.f;
+                    const float x = *reinterpret_cast<const float *>(xtile + (xoff[i] + (uint32_t)(k + j < K ? k + j : 0) * 4u));
+                    v[j] = (xok[i] && k + j < K) ? x : 0.f;
                 }
             }
             st[i] = v;
@@ -216,7 +223,7 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
         // wait counter with the LDS reads.
         const uint32_t *set_words = reinterpret_cast<const uint32_t *>(a.masks) + (size_t)c0 * 4 + (lane & (4 * NCW - 1));
         auto load_sets = [&](int kb) { return (int)set_words[(size_t)kb * n_pad * 4]; };
-        int sets_cur = load_sets(kb0), sets_next = sets_cur;
+        int sets_ahead = load_sets(kb0);   // the sets of the block the NEXT stage works on (here: of the first stage)
         TileView view;
         view.tile = lds;
         view.stride_vgpr = RB;
@@ -235,12 +242,13 @@ __global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
             // The two workgroups that share a compute unit take turns in issue priority, stage by stage: the
             // hardware would otherwise always prefer the older one, which then finishes long before the other.
             if ((((stage - s0) >> 1) + wg_parity) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-            stage_load(stage + 1 < s1 ? stage + 1 : stage);   // behind the last stage: repeated, not used
-            if (half == 0) {
-                sets_cur = sets_next;
-                const int kb = stage >> 1;
-                sets_next = load_sets(kb + 1 < kb1 ? kb + 1 : kb);   // behind the last block: repeated, not used
-            }
+            // Every stage issues the same three requests in the same order (tile of the next stage, row sets of the
+            // next stage's block -- the same block again after a low half), without branches around them, so that
+            // the wait counters can tell the sets of this stage have arrived without waiting for the new requests.
+            const int sets_cur = sets_ahead;
+            const int next_stage = stage + 1 < s1 ? stage + 1 : stage;   // behind the last stage: repeated, not used
+            stage_load(next_stage);
+            sets_ahead = load_sets(next_stage >> 1);
             view.lane_base = lane_base + ((stage - s0) & 1) * TILE;
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
