@@ -72,7 +72,7 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
 /*
  * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
  * the four TCSC arrays unchanged (read by the small-M kernel), their K-blocked form (read by
- * the large-M kernel) and a workspace for split-K partial sums.  K-blocking follows the idea
+ * the large-M kernel) and the workspace of tstgemm().  K-blocking follows the idea
  * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block = 64 rows
  * so that all X entries one block touches fit in the LDS, every column's two lists are cut at
  * the block borders, and the pieces are stored block after block.  A piece holds at most 64
@@ -81,7 +81,8 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *
  *   masks      uint64 [n_kblocks][n_pad][2]   [kb][n][0]: the +1 rows of column n inside K-block
  *                                             kb, [kb][n][1]: the -1 rows
- *   workspace  bytes  [workspace_bytes]       split-K partial sums and arrival counters of tstgemm()
+ *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): arrival counters, split-K partial sums and a
+ *                                             transposed copy of (a slab of rows of) X
  * n_pad = N rounded up to a multiple of 64; columns >= N have empty sets.
  */
 typedef struct tcsc_layout {
@@ -115,7 +116,7 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * parameters; repeated calls give bit-identical results.  Integer-valued inputs small enough
  * for fp32 give exact results.
  * Two calls that use the same handle must be ordered (same stream, or an event between them):
- * they share the handle's split-K workspace.
+ * they share the handle's workspace.
  */
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 

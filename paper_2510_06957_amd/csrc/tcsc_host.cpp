@@ -30,8 +30,8 @@ void compute_layout(tcsc *t)
     l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + 4));
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + 4));
     l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
-    l.off_workspace = place(tst::kWorkspaceBytes);
-    l.workspace_bytes = tst::kWorkspaceBytes;
+    l.workspace_bytes = tst::workspace_bytes(l.n_kblocks);
+    l.off_workspace = place(l.workspace_bytes);
     l.total_bytes = off;
 }
 
@@ -201,7 +201,6 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
     if (copy(l.off_row_index_neg, t->row_index_neg) != hipSuccess) return TSTGEMM_EHIP;
     // The sources are pageable host memory: wait until the copies have read them.
     if (hipStreamSynchronize(s) != hipSuccess) return TSTGEMM_EHIP;
-    if (hipMemsetAsync(d + l.off_workspace, 0, tst::kCounterBytes, s) != hipSuccess) return TSTGEMM_EHIP;
     if (tst::launch_reblock(t, s) != hipSuccess) return TSTGEMM_EHIP;
     t->uploaded = true;
     return TSTGEMM_OK;

@@ -12,10 +12,16 @@ namespace tst {
 // Geometry of the K-blocked device form (see tcsc_layout_t in tstgemm.h).
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
-constexpr int kMaxSplitGroups = 512;                     // workgroups of a split-K launch never exceed this
-constexpr size_t kPartialTileBytes = 64 * 256 * 4;       // 64 columns x 256 rows of fp32 partial sums
-constexpr size_t kCounterBytes = kMaxSplitGroups * sizeof(int32_t);
-constexpr size_t kWorkspaceBytes = kCounterBytes + kMaxSplitGroups * kPartialTileBytes;
+constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: [k_slices][padded rows][n_pad] fp32
+constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
+
+// The copy holds whole row tiles of X over all (padded) K: at least one tile of 256 rows must fit.
+inline size_t xt_bytes(int n_kblocks)
+{
+    const size_t one = (size_t)256 * n_kblocks * kKBlock * sizeof(float);
+    return one > kXtMinBytes ? one : kXtMinBytes;
+}
+inline size_t workspace_bytes(int n_kblocks) { return kPartialBytes + xt_bytes(n_kblocks); }
 
 }  // namespace tst
 
@@ -33,8 +39,9 @@ namespace tst {
 struct DeviceTcsc {
     const int32_t *col_start_pos, *col_start_neg, *row_index_pos, *row_index_neg;
     unsigned long long *masks;   // [n_kblocks][n_pad][2]
-    int32_t *counters;   // kMaxSplitGroups arrival counters, zero between calls
     float *partials;     // split-K partial sums
+    float *xt;           // xt[tile][k][row]: row tiles of (a slab of) X, transposed, zero padded
+    size_t xt_capacity;  // bytes
 };
 
 inline DeviceTcsc device_view(const tcsc *t)
@@ -46,8 +53,9 @@ inline DeviceTcsc device_view(const tcsc *t)
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_pos),
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_neg),
                       reinterpret_cast<unsigned long long *>(d + l.off_masks),
-                      reinterpret_cast<int32_t *>(d + l.off_workspace),
-                      reinterpret_cast<float *>(d + l.off_workspace + kCounterBytes)};
+                      reinterpret_cast<float *>(d + l.off_workspace),
+                      reinterpret_cast<float *>(d + l.off_workspace + kPartialBytes),
+                      xt_bytes(l.n_kblocks)};
 }
 
 // reblock.hip -- GPU pass: TCSC arrays (already on the device) -> per-K-block row sets.

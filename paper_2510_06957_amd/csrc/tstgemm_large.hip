@@ -1,32 +1,37 @@
-// Large-M kernel of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper) for gfx950.
+// Large-M kernels of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper) for gfx950.
 //
 // Arithmetic is that of BaseTCSC (Sec. 2): every output is a sum of gathered X entries
 // (+1 list) minus a sum of gathered X entries (-1 list), bias added once at the end; no
 // multiplications.  The mapping to the machine is this library's own:
 //
-//   * one lane owns R consecutive rows of X (R = 1, 2 or 4), a wavefront therefore owns a
-//     tile of TM = 64 R rows, and walks the index lists of its columns with a wave-uniform
-//     index: one index serves all TM rows (the paper's "vertical" SIMD scheme and its
-//     M-unrolling, Sec. 3, carried to 64 lanes);
-//   * K is cut into blocks of 64 (the paper's blocking idea, Sec. 3 "Blocking"); the
-//     workgroup keeps the X tile of the current block transposed in the LDS, tile[k][row], so
-//     the gather of one index is a single conflict-free ds_read (b32/b64/b128) per lane;
-//   * gathers are issued eight at a time and added after one wait; the latency of a group is
-//     covered by the other wavefronts (the kernel is built for 8 wavefronts per SIMD: at most
-//     64 VGPRs, two workgroups of 16 wavefronts per compute unit);
-//   * a list piece (one column, one K-block, one sign) arrives as a 64-bit row set; the scalar
-//     unit turns it into row numbers with find-first-set / clear-bit, so an index costs two
-//     SALU instructions and neither VALU work, LDS traffic nor memory latency.  The sets of
-//     a wavefront's columns for the next K-block are fetched one K-block ahead with one vector
-//     load and moved to scalar registers with a few v_readlane at the block border;
-//   * the X tile itself is not prefetched: two workgroups share a compute unit, one computes
-//     while the other exchanges its tile between two barriers;
+//   * k_pack_x copies X into the workspace as row tiles, transposed: xt[tile][k][row], a tile
+//     being TM = 64 R consecutive rows of X (R = 1, 2 or 4), K padded to whole K-blocks, rows
+//     beyond M and entries beyond K zero.  A K-block of a tile (64 x TM floats) is then one
+//     contiguous piece of memory that goes into the LDS with plain 16-byte copies, and the
+//     strided walk over the rows of X happens once per call instead of once per workgroup;
+//   * in k_large one lane owns R consecutive rows of X, a wavefront therefore owns a whole tile,
+//     and walks the index lists of its NCW columns with a wave-uniform index: one index serves
+//     all TM rows (the paper's "vertical" SIMD scheme and its M-unrolling, Sec. 3, carried to
+//     64 lanes); the gather of one index is a single conflict-free ds_read (b32/b64/b128);
+//   * K is cut into blocks of 64 (the paper's blocking idea, Sec. 3 "Blocking"); a workgroup
+//     (16 wavefronts = 16 NCW columns) keeps one K-block of its tile in the LDS, in front of it
+//     a row of zeros;
+//   * a list piece (one column, one K-block, one sign) arrives as a 64-bit row set, fetched by
+//     the scalar unit; the scalar unit turns it into row numbers with find-first-set /
+//     clear-bit, so an index costs two SALU instructions and neither VALU work, LDS traffic nor
+//     memory latency.  An exhausted set yields row -1, the row of zeros: pieces are padded to
+//     a multiple of four gathers that way (the paper pads its interleaved groups with a dummy
+//     zero index for the same reason, Sec. 3), which leaves only two group sizes, 8 and 4;
+//   * the gathers of a group are all issued before the first addition; the latency of a group
+//     is covered by the other wavefronts: the kernel is built for 8 wavefronts per SIMD (at
+//     most 64 VGPRs, two workgroups per compute unit).  While one workgroup exchanges its tile
+//     between two barriers, the other one computes;
 //   * accumulators stay in VGPRs over all K-blocks of the workgroup's K slice; the bias add and
 //     the store are fused;
 //   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
 //     8 slices handled by different workgroups; each writes its partial sums to the workspace,
-//     and the workgroup that arrives last adds the slices in slice order, adds the bias and
-//     stores Y -- a fixed summation order, so results do not depend on timing.
+//     and k_reduce adds the slices in slice order, adds the bias and stores Y -- a fixed
+//     summation order, so results do not depend on timing, and no atomics or fences.
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -35,9 +40,11 @@ int g_cols_per_wave = 0, g_k_slices = 0;
 
 namespace {
 
-constexpr int NW = 16;   // wavefronts per workgroup
-typedef int int4v __attribute__((ext_vector_type(4)));
+constexpr int NW = 16;        // wavefronts per workgroup
+constexpr int NT = NW * 64;   // threads per workgroup
 typedef float float4v __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+typedef const __attribute__((address_space(4))) u64 *const_u64_ptr;   // read through the scalar cache
 
 template <int R> struct RowVec;
 template <> struct RowVec<1> { typedef float type; };
@@ -53,50 +60,46 @@ template <int R> __device__ __forceinline__ typename RowVec<R>::type zero_vec()
     if constexpr (R == 1) return 0.f; else return typename RowVec<R>::type(0.f);
 }
 
-// A stage of the kernel covers half a K-block: 32 rows of W, one 32-bit half of a 64-bit row set.
-constexpr int kStageRows = kKBlock / 2;
+// A tile row (one k, TM = 64 R rows of X) is 256 R bytes: 2^(8 + log2 R).
+template <int R> constexpr int row_shift() { return R == 4 ? 10 : R == 2 ? 9 : 8; }
 
-// Smallest member of a non-empty row set, removed from the set: two SALU instructions (find-first-set, clear bit).
-__device__ __forceinline__ int pop_lowest(uint32_t &set)
+__device__ __forceinline__ int members(u64 set)
 {
-    const int k = __builtin_ctz(set);
-    asm("s_bitset0_b32 %0, %1" : "+s"(set) : "s"(k));
+    int n;
+    asm("s_bcnt1_i32_b64 %0, %1" : "=s"(n) : "s"(set) : "scc");
+    return n;
+}
+
+// Smallest member of a row set, removed from the set: two SALU instructions (find-first-set, clear bit).  The empty
+// set yields -1 and stays empty (the bit cleared is then bit 63).
+__device__ __forceinline__ int pop_lowest(u64 &set)
+{
+    int k;
+    asm("s_ff1_i32_b64 %0, %1" : "=s"(k) : "s"(set));
+    asm("s_bitset0_b64 %0, %1" : "+s"(set) : "s"(k));
     return k;
 }
 
-// LDS layout of an X tile: tile row k (one column of X, TM = 64 R consecutive rows of X) starts at k * stride,
-// stride = 4 TM + 16 bytes.  The 16 bytes of padding rotate the banks by four from one tile row to the next, so
-// that the transposing writes of the staging (lanes that differ in k and in the X row) hit 64 different banks,
-// while a gather (all lanes the same k, consecutive X rows) stays contiguous and 16-byte aligned.
-template <int R> constexpr int tile_stride() { return 256 * R + 16; }
-
-// This lane's R rows of tile row k: address = k * stride + lane_base in one VALU instruction (k is wave-uniform).
+// This lane's R rows of tile row k: address = (k << row_shift) + lane_base in one VALU instruction (k is wave-uniform).
+// lane_base points at tile row 0; row -1, right in front of it, holds zeros.
 template <int R>
-__device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int stride_vgpr, int k)
+__device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int k)
 {
     int off;
-    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "s"(k), "v"(stride_vgpr), "v"(lane_base));
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(off) : "s"(k), "n"(row_shift<R>()), "v"(lane_base));
     return *reinterpret_cast<const typename RowVec<R>::type *>(tile + off);
 }
 
-// What a gather needs besides the row number: the tile, this lane's byte offset inside a tile row (plus the offset of
-// the buffer in use), and the row stride held in a VGPR (the multiply-add takes only one scalar operand).
-struct TileView {
-    const char *tile;
-    int lane_base;
-    int stride_vgpr;
-};
-
-// acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it; the set has at
-// least COUNT members).  All gathers are issued before the first addition, so COUNT LDS reads are in flight at once;
-// with 8 wavefronts per SIMD the other wavefronts keep the LDS busy while this one adds.
+// acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it); when the set has
+// fewer members the rest of the group gathers the row of zeros.  All gathers are issued before the first addition, so
+// COUNT LDS reads are in flight at once.
 template <int R, bool NEG, int COUNT>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const TileView &t, uint32_t &set)
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile, int lane_base, u64 &set)
 {
     typedef typename RowVec<R>::type V;
     V v[COUNT];
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(t.tile, t.lane_base, t.stride_vgpr, pop_lowest(set));
+    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile, lane_base, pop_lowest(set));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < COUNT; ++i) {
@@ -105,227 +108,222 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const Tile
 }
 
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
-// in groups of 8 and a remainder of 4 + 2 + 1.  The set is wave-uniform.
+// in groups of 8 and, if five or more members are left over, one more group of 8, else a group of 4.  The set is
+// wave-uniform.
 template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, uint32_t set, const TileView &t)
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile, int lane_base)
 {
-    int n = __builtin_popcount(set);
-    while (n >= 8) {
-        gather<R, NEG, 8>(acc, t, set);
+    int n = members(set);
+    while (n > 4) {
+        gather<R, NEG, 8>(acc, tile, lane_base, set);
         n -= 8;
     }
-    if (n & 4) gather<R, NEG, 4>(acc, t, set);
-    if (n & 2) gather<R, NEG, 2>(acc, t, set);
-    if (n & 1) gather<R, NEG, 1>(acc, t, set);
+    if (n > 0) gather<R, NEG, 4>(acc, tile, lane_base, set);
 }
 
+// ------------------------------------------------------------------------------------------------------------------
+// k_pack_x: X (rows m_begin .. m_begin + rows) -> xt[tile][k_pad][TM], zero padded.  One workgroup per (K-block,
+// 64 rows): 64 x 64 floats go through the LDS so that both the reads (along k) and the writes (along rows) are
+// contiguous.  VEC: rows of X are 16-byte aligned and K is a multiple of 4.
+constexpr int kPackThreads = 256;
+
+template <bool VEC>
+__global__ void __launch_bounds__(kPackThreads)
+k_pack_x(const float *__restrict__ X, float *__restrict__ xt, int rows, int K, int k_pad, int TM)
+{
+    __shared__ float t[64][65];
+    const int kb = blockIdx.x, m0 = blockIdx.y * 64;
+    const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
+    const int k = kb * 64 + 4 * c;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int row = r + 16 * p, m = m0 + row;
+        float4v v = {0.f, 0.f, 0.f, 0.f};
+        if (m < rows) {
+            const float *src = X + (size_t)m * K + k;
+            if constexpr (VEC) {
+                if (k < K) v = *reinterpret_cast<const float4v *>(src);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (k + j < K) v[j] = src[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t[4 * c + j][row] = v[j];
+    }
+    __syncthreads();
+    const int kk = threadIdx.x >> 2, q = threadIdx.x & 3;
+    const int tile = m0 / TM, r0 = m0 % TM;
+    float *dst = xt + ((size_t)tile * k_pad + (size_t)kb * 64 + kk) * TM + r0 + 16 * q;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float4v o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = t[kk][16 * q + 4 * i + j];
+        *reinterpret_cast<float4v *>(dst + 4 * i) = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
 struct LargeArgs {
-    const float *X;
-    const unsigned long long *masks;
+    const float *xt;
+    const u64 *masks;
     const float *b;
     float *Y;
-    float *partials;
-    int32_t *counters;
-    int M, K, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
-    int wg_slots;   // workgroups of one dispatch round: blocks i and i + wg_slots tend to share a compute unit
+    float *partials;   // [k_slices][rows_pad][n_pad] when k_slices > 1
+    int M, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice, rows_pad;
+    int remap;   // workgroups per XCD when the grid is spread evenly over the 8 XCDs, else 0
 };
 
-// R rows per lane, NCW columns per wavefront; VEC: X rows are 16-byte aligned and K is a multiple of 4, so X is
-// staged with 16-byte loads (otherwise element by element).
-template <int R, int NCW, bool VEC>
-__global__ void __launch_bounds__(NW * 64, 8) k_large(const LargeArgs a)
+// R rows per lane, NCW columns per wavefront.
+template <int R, int NCW>
+__global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
-    constexpr int TM = 64 * R;            // rows of X per workgroup tile
-    constexpr int RB = tile_stride<R>();         // bytes from one tile row (one k, TM rows) to the next
-    constexpr int TILE = kStageRows * RB;        // bytes of one buffer
-    constexpr int NT = NW * 64;
-    constexpr int PIECES = kStageRows / 4;       // 16-byte pieces of an X row per stage
-    constexpr int ROWS_PER_PASS = NT / PIECES;   // X rows the workgroup fetches with one load per thread
-    constexpr int CPT = (TM + ROWS_PER_PASS - 1) / ROWS_PER_PASS;   // loads per thread and stage
-    __shared__ __attribute__((aligned(16))) char lds[2 * TILE];
-    __shared__ int last_flag;
+    constexpr int TM = 64 * R;                 // rows of X per workgroup tile
+    constexpr int RB = TM * 4;                 // bytes of a tile row
+    constexpr int STAGE = kKBlock * RB;        // bytes of one K-block of the tile
+    constexpr int LPT = STAGE / (NT * 16);     // 16-byte pieces per thread and K-block
+    static_assert(LPT >= 1 && STAGE % (NT * 16) == 0, "staging layout");
+    __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then tile rows 0 .. 63
+    char *const tile = lds + RB;
 
-    const float *__restrict__ X = a.X;
-    const int M = a.M, K = a.K, N = a.N, n_pad = a.n_pad;
-
+    const int M = a.M, N = a.N;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int cg = blockIdx.x % a.n_colgroups;
-    const int rest = blockIdx.x / a.n_colgroups;
+
+    // Consecutive workgroup numbers go to different XCDs (each with its own L2).  Workgroups that share a K slice of
+    // a tile read the same part of xt, so they are renumbered to land on the same XCD.
+    int wg = blockIdx.x;
+    if (a.remap) wg = (wg & 7) * a.remap + (wg >> 3);
+    const int cg = wg % a.n_colgroups;
+    const int rest = wg / a.n_colgroups;
     const int slice = rest % a.k_slices, mt = rest / a.k_slices;
     const int m0 = mt * TM;
     const int c0 = (cg * NW + wave) * NCW;   // < n_pad by construction of the grid
     const int kb0 = min(slice * a.kb_per_slice, a.n_kblocks);
     const int kb1 = min(kb0 + a.kb_per_slice, a.n_kblocks);
 
-    // ---- staging role of this thread.  A stage needs 32 consecutive floats (8 pieces of 16 bytes) of every X row
-    // of the tile.  Four neighbouring lanes fetch 64 contiguous bytes of one row, so a wavefront load touches 16
-    // rows; thread t owns piece (t & 3) + 4 * ((t >> 2) / ROWS...) -- in short: row srow + i * ROWS_PER_PASS, piece
-    // spiece, for i < CPT.
-    const int spiece = (threadIdx.x & 3) + 4 * ((threadIdx.x >> 2) / ROWS_PER_PASS % (PIECES / 4));
-    const int srow = (threadIdx.x >> 2) % ROWS_PER_PASS + ROWS_PER_PASS * ((threadIdx.x >> 2) / ROWS_PER_PASS / (PIECES / 4));
-    static_assert(PIECES == 8 && NT % PIECES == 0, "staging layout");
-    float4v st[CPT];
-
-    // Loads are issued unconditionally (out-of-range rows and columns read a clamped, valid address and are zeroed
-    // afterwards): the wait counters then know exactly how many loads are in flight behind a given one.
-    // Byte offsets of this thread's X rows from the first row of the tile, as 32-bit values next to a wave-uniform
-    // 64-bit base (rows beyond M point at the last valid row and are zeroed after the load).
-    const char *xtile = reinterpret_cast<const char *>(X + (size_t)m0 * K);
-    uint32_t xoff[CPT];
-    bool xok[CPT];
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-        const int row = srow + i * (NT / 4 / (PIECES / 4));
-        xok[i] = row < TM && m0 + row < M;
-        xoff[i] = (uint32_t)(min(row, M - 1 - m0)) * (uint32_t)K * 4u;
-    }
-    auto stage_load = [&](int stage) {
-        const int k = stage * kStageRows + 4 * spiece;
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            float4v v;
-            if constexpr (VEC) {
-                const bool ok = xok[i] && k < K;   // K % 4 == 0: a piece is inside or outside as a whole
-                v = *reinterpret_cast<const float4v *>(xtile + (xoff[i] + (uint32_t)(k < K ? k : 0) * 4u));
-                if (!ok) v = float4v{0.f, 0.f, 0.f, 0.f};
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float x = *reinterpret_cast<const float *>(xtile + (xoff[i] + (uint32_t)(k + j < K ? k + j : 0) * 4u));
-                    v[j] = (xok[i] && k + j < K) ? x : 0.f;
-                }
-            }
-            st[i] = v;
-        }
-    };
-    auto stage_store = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int row = srow + i * (NT / 4 / (PIECES / 4));
-            if (row < TM) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<float *>(lds + buf * TILE + (4 * spiece + j) * RB + row * 4) = st[i][j];
-            }
-        }
-    };
-
-    // ---- compute role: columns c0 .. c0+NCW-1, rows m0 + R*lane .. + R-1
     V acc[NCW];
 #pragma unroll
     for (int j = 0; j < NCW; ++j) acc[j] = zero_vec<R>();
 
     if (kb0 < kb1) {
-        // Row sets of (kb, c0 .. c0+NCW-1): 4*NCW consecutive dwords (column j: +1 set low/high half, -1 set low/high
-        // half), fetched by lanes 0 .. 4*NCW-1 of one vector load a K-block ahead.  A scalar load would share its
-        // wait counter with the LDS reads.
-        const uint32_t *set_words = reinterpret_cast<const uint32_t *>(a.masks) + (size_t)c0 * 4 + (lane & (4 * NCW - 1));
-        auto load_sets = [&](int kb) { return (int)set_words[(size_t)kb * n_pad * 4]; };
-        int sets_ahead = load_sets(kb0);   // the sets of the block the NEXT stage works on (here: of the first stage)
-        TileView view;
-        view.tile = lds;
-        view.stride_vgpr = RB;
-        const int lane_base = lane * (R * 4);
-        const int wg_parity = (blockIdx.x / a.wg_slots) & 1;
+        // ---- staging: K-block kb of the tile is STAGE contiguous bytes of xt; thread t copies pieces t, t + NT, ...
+        const char *xtile = reinterpret_cast<const char *>(a.xt) + (size_t)mt * a.n_kblocks * STAGE;
+        const int piece = threadIdx.x * 16;
+        float4v st[LPT];
+        auto stage_load = [&](int kb) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i)
+                st[i] = *reinterpret_cast<const float4v *>(xtile + (size_t)kb * STAGE + (piece + i * NT * 16));
+        };
+        auto stage_store = [&]() {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) *reinterpret_cast<float4v *>(tile + piece + i * NT * 16) = st[i];
+        };
+        // ---- row sets of (kb, c0 .. c0+NCW-1): 2 NCW consecutive 64-bit words (column j: +1 set, -1 set)
+        const const_u64_ptr sets_base =
+            reinterpret_cast<const_u64_ptr>(reinterpret_cast<uintptr_t>(a.masks)) + (size_t)c0 * 2;
+        const size_t sets_stride = (size_t)a.n_pad * 2;
+        u64 sets[2 * NCW];
+        auto load_sets = [&](int kb) {
+#pragma unroll
+            for (int i = 0; i < 2 * NCW; ++i) sets[i] = sets_base[(size_t)kb * sets_stride + i];
+        };
 
-        // Stages: two per K-block (its low and its high 32 rows), double-buffered in the LDS.  While a stage is
-        // computed the X tile of the next one sits in registers (requested at the start of the stage) and is written
-        // to the other buffer at the end; one barrier per stage.
-        const int s0 = 2 * kb0, s1 = 2 * kb1;
-        stage_load(s0);
-        stage_store(0);
+        if (threadIdx.x < RB / 4) reinterpret_cast<float *>(lds)[threadIdx.x] = 0.f;
+        load_sets(kb0);
+        stage_load(kb0);
+        stage_store();
         __syncthreads();
-        for (int stage = s0; stage < s1; ++stage) {
-            const int half = stage & 1;
-            // The two workgroups that share a compute unit take turns in issue priority, stage by stage: the
-            // hardware would otherwise always prefer the older one, which then finishes long before the other.
-            if ((((stage - s0) >> 1) + wg_parity) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-            // Every stage issues the same three requests in the same order (tile of the next stage, row sets of the
-            // next stage's block -- the same block again after a low half), without branches around them, so that
-            // the wait counters can tell the sets of this stage have arrived without waiting for the new requests.
-            const int sets_cur = sets_ahead;
-            const int next_stage = stage + 1 < s1 ? stage + 1 : stage;   // behind the last stage: repeated, not used
-            stage_load(next_stage);
-            sets_ahead = load_sets(next_stage >> 1);
-            view.lane_base = lane_base + ((stage - s0) & 1) * TILE;
+        const int lane_base = RB + lane * (R * 4);
+        for (int kb = kb0; kb < kb1; ++kb) {
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane(sets_cur, 4 * j + half);
-                const uint32_t neg = (uint32_t)__builtin_amdgcn_readlane(sets_cur, 4 * j + 2 + half);
-                run_list<R, false>(acc[j], pos, view);
-                run_list<R, true>(acc[j], neg, view);
+                run_list<R, false>(acc[j], sets[2 * j], lds, lane_base);
+                run_list<R, true>(acc[j], sets[2 * j + 1], lds, lane_base);
             }
-            if (stage + 1 < s1) stage_store(((stage - s0) & 1) ^ 1);
+            if (kb + 1 == kb1) break;
+            // Exchange the tile.  The requests for the next K-block go out before the barrier, into the registers
+            // the gathers no longer need, so their latency runs while the slower wavefronts finish; the barrier
+            // itself only has to order this wavefront's LDS reads (complete: their values have been added) before
+            // the other wavefronts' writes, so it does not wait for the requests.
+            load_sets(kb + 1);
+            stage_load(kb + 1);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            stage_store();
             __syncthreads();
         }
     }
 
-    // ---- split K: publish this slice's partial sums; the last workgroup of the group sums all slices in order
-    if (a.k_slices > 1) {
-        const int group = mt * a.n_colgroups + cg;
-        constexpr size_t kSliceFloats = (size_t)NW * NCW * TM;
-        float *gbase = a.partials + (size_t)group * a.k_slices * kSliceFloats + (size_t)(wave * NCW) * TM + lane * R;
-#pragma unroll
-        for (int j = 0; j < NCW; ++j)
-            *reinterpret_cast<V *>(gbase + (size_t)slice * kSliceFloats + (size_t)j * TM) = acc[j];
-        // Release / acquire through one thread: the barrier orders the workgroup's stores before thread 0's
-        // device-scope fence, and thread 0's fence after the counter update before the workgroup's loads.
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            __threadfence();
-            const int arrived = atomicAdd(&a.counters[group], 1);
-            const int last = arrived == a.k_slices - 1;
-            if (last) {
-                a.counters[group] = 0;   // ready for the next call
-                __threadfence();
-            }
-            last_flag = last;
-        }
-        __syncthreads();
-        if (!last_flag) return;
-        // All slices of a column are requested before the first addition (one memory round trip instead of
-        // k_slices); the additions then run in slice order.
-        constexpr int kMaxSlices = 8;
-#pragma unroll
-        for (int j = 0; j < NCW; ++j) {
-            V part[kMaxSlices];
-#pragma unroll
-            for (int s = 0; s < kMaxSlices; ++s)
-                part[s] = *reinterpret_cast<const V *>(gbase + (size_t)(s < a.k_slices ? s : 0) * kSliceFloats +
-                                                       (size_t)j * TM);
-            V sum = zero_vec<R>();
-#pragma unroll
-            for (int s = 0; s < kMaxSlices; ++s)
-                if (s < a.k_slices) sum += part[s];
-            acc[j] = sum;
-        }
-    }
-
-    // ---- epilogue: Y = acc + b, bias added once, last
+    // ---- output: Y = acc + b (bias added once, last), or this K slice's partial sums for k_reduce
+    const bool partial = a.k_slices > 1;
+    float *out = partial ? a.partials + (size_t)slice * a.rows_pad * a.n_pad : a.Y;
+    const int ld = partial ? a.n_pad : N;          // row stride
+    const int m_end = partial ? a.rows_pad : M;    // the partial buffers have whole tiles and padded columns
+    const int n_end = partial ? a.n_pad : N;
     float bias[NCW];
 #pragma unroll
-    for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
+    for (int j = 0; j < NCW; ++j) bias[j] = (!partial && a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
     const bool store_vec =
-        NCW == 4 && (N % 4 == 0) && (c0 + 4 <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
+        NCW == 4 && (ld % 4 == 0) && (c0 + 4 <= n_end) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int m = m0 + lane * R + r;
-        if (m >= M) continue;
-        float *yrow = a.Y + (size_t)m * N + c0;
+        if (m >= m_end) continue;
+        float *yrow = out + (size_t)m * ld + c0;
         if constexpr (NCW == 4) {
             if (store_vec) {
                 float4v o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = lane_of<R>(acc[j], r) + bias[j];
+                for (int j = 0; j < 4; ++j) o[j] = partial ? lane_of<R>(acc[j], r) : lane_of<R>(acc[j], r) + bias[j];
                 *reinterpret_cast<float4v *>(yrow) = o;
                 continue;
             }
         }
 #pragma unroll
         for (int j = 0; j < NCW; ++j)
-            if (c0 + j < N) yrow[j] = lane_of<R>(acc[j], r) + bias[j];
+            if (c0 + j < n_end) yrow[j] = partial ? lane_of<R>(acc[j], r) : lane_of<R>(acc[j], r) + bias[j];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b.  One thread per four consecutive columns of a row.
+constexpr int kReduceThreads = 256;
+constexpr int kMaxSlices = 8;
+
+__global__ void __launch_bounds__(kReduceThreads)
+k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__restrict__ Y, int M, int N, int n_pad,
+         int rows_pad, int k_slices, int vec_store)
+{
+    const int quads = n_pad / 4;
+    const long long id = (long long)blockIdx.x * kReduceThreads + threadIdx.x;
+    const int m = (int)(id / quads), c = (int)(id % quads) * 4;
+    if (m >= M || c >= N) return;
+    const size_t slice_floats = (size_t)rows_pad * n_pad;
+    const float *src = P + (size_t)m * n_pad + c;
+    // all slices are requested before the first addition; the additions then run in slice order
+    float4v part[kMaxSlices];
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        part[s] = *reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * slice_floats);
+    float4v sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        if (s < k_slices) sum += part[s];
+    float *dst = Y + (size_t)m * N + c;
+    if (vec_store && c + 4 <= N) {
+        float4v bias = {0.f, 0.f, 0.f, 0.f};
+        if (b) bias = *reinterpret_cast<const float4v *>(b + c);
+        *reinterpret_cast<float4v *>(dst) = sum + bias;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (c + j < N) dst[j] = sum[j] + (b ? b[c + j] : 0.f);
     }
 }
 
@@ -343,54 +341,90 @@ int compute_units()
     return cus;
 }
 
+// One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles must fit the workspace.
 template <int R, int NCW>
-hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M, int k_slices, hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int rows, int k_slices, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
     constexpr int TM = 64 * R;
+    const int k_pad = l.n_kblocks * kKBlock;
+    const long long m_tiles = (rows + TM - 1) / TM;
+    if ((size_t)m_tiles * k_pad * TM * sizeof(float) > d.xt_capacity) return hipErrorInvalidValue;
+
+    const bool vec = (l.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const dim3 pgrid((unsigned)l.n_kblocks, (unsigned)(m_tiles * (TM / 64)));
+    if (pgrid.y > 65535u) return hipErrorInvalidValue;
+    if (vec)
+        hipLaunchKernelGGL((k_pack_x<true>), pgrid, dim3(kPackThreads), 0, stream, X, d.xt, rows, l.K, k_pad, TM);
+    else
+        hipLaunchKernelGGL((k_pack_x<false>), pgrid, dim3(kPackThreads), 0, stream, X, d.xt, rows, l.K, k_pad, TM);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
     LargeArgs a;
-    a.X = X; a.masks = d.masks; a.b = b; a.Y = Y;
-    a.partials = d.partials; a.counters = d.counters;
-    a.M = M; a.K = l.K; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
+    a.xt = d.xt; a.masks = d.masks; a.b = b; a.Y = Y;
+    a.partials = d.partials;
+    a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
-    const long long m_tiles = (M + TM - 1) / TM;
+    a.rows_pad = (int)(m_tiles * TM);
     const long long groups = m_tiles * a.n_colgroups;
-    if (k_slices > 1 && groups * k_slices > kMaxSplitGroups) k_slices = (int)(kMaxSplitGroups / groups);
+    if (k_slices > kMaxSlices) k_slices = kMaxSlices;
+    const size_t slice_bytes = (size_t)a.rows_pad * l.n_pad * sizeof(float);
+    if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
-    a.wg_slots = compute_units();
     const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    const bool vec = (l.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    if (vec)
-        hipLaunchKernelGGL((k_large<R, NCW, true>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
-    else
-        hipLaunchKernelGGL((k_large<R, NCW, false>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
+    a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
+    hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess || k_slices == 1) return e;
+
+    const long long quads = (long long)rows * (l.n_pad / 4);
+    const int vec_store = (l.N % 4 == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0) &&
+                          (b == nullptr || (reinterpret_cast<uintptr_t>(b) & 15) == 0);
+    hipLaunchKernelGGL(k_reduce, dim3((unsigned)((quads + kReduceThreads - 1) / kReduceThreads)), dim3(kReduceThreads), 0,
+                       stream, d.partials, b, Y, rows, l.N, l.n_pad, a.rows_pad, k_slices, vec_store);
     return hipGetLastError();
 }
 
 // Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave
-// compute units idle, into as few slices as fill them.
+// compute units idle, into as few slices as fill them.  X is processed in slabs of as many row tiles as the
+// workspace holds.
 template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
+    const DeviceTcsc d = device_view(t);
+    constexpr int TM = 64 * R;
     const int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
-    const long long m_tiles = (M + 64 * R - 1) / (64 * R);
-    const long long groups = m_tiles * (l.n_pad / (NW * ncw));
-    int k_slices = g_k_slices;
-    if (k_slices == 0) {
-        const int slots = 2 * compute_units();   // two workgroups per compute unit
-        k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
-        if (k_slices > 8) k_slices = 8;
+    const size_t tile_bytes = (size_t)l.n_kblocks * kKBlock * TM * sizeof(float);
+    long long slab_rows = (long long)(d.xt_capacity / tile_bytes) * TM;
+    if (slab_rows < TM) return hipErrorInvalidValue;
+    if (slab_rows > 65535LL * 64) slab_rows = 65535LL * 64 / TM * TM;
+    for (long long m_begin = 0; m_begin < M; m_begin += slab_rows) {
+        const int rows = (int)((M - m_begin) < slab_rows ? (M - m_begin) : slab_rows);
+        const long long m_tiles = (rows + TM - 1) / TM;
+        const long long groups = m_tiles * (l.n_pad / (NW * ncw));
+        int k_slices = g_k_slices;
+        if (k_slices == 0) {
+            const int slots = 2 * compute_units();   // two workgroups per compute unit
+            k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
+            if (k_slices > 8) k_slices = 8;
+        }
+        if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;
+        const float *Xs = X + (size_t)m_begin * l.K;
+        float *Ys = Y + (size_t)m_begin * l.N;
+        hipError_t e;
+        switch (ncw) {
+        case 1: e = launch<R, 1>(Xs, t, b, Ys, rows, k_slices, stream); break;
+        case 2: e = launch<R, 2>(Xs, t, b, Ys, rows, k_slices, stream); break;
+        default: e = launch<R, 4>(Xs, t, b, Ys, rows, k_slices, stream); break;
+        }
+        if (e != hipSuccess) return e;
     }
-    if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;
-    switch (ncw) {
-    case 1: return launch<R, 1>(X, t, b, Y, M, k_slices, stream);
-    case 2: return launch<R, 2>(X, t, b, Y, M, k_slices, stream);
-    default: return launch<R, 4>(X, t, b, Y, M, k_slices, stream);
-    }
+    return hipSuccess;
 }
 
 }  // namespace
