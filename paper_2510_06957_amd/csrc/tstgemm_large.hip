@@ -70,55 +70,53 @@ __device__ __forceinline__ int members(u64 set)
     return n;
 }
 
-// Smallest member of a row set, removed from the set: two SALU instructions (find-first-set, clear bit).  The empty
-// set yields -1 and stays empty (the bit cleared is then bit 63).
-__device__ __forceinline__ int pop_lowest(u64 &set)
-{
-    int k;
-    asm("s_ff1_i32_b64 %0, %1" : "=s"(k) : "s"(set));
-    asm("s_bitset0_b64 %0, %1" : "+s"(set) : "s"(k));
-    return k;
-}
-
-// This lane's R rows of tile row k: address = (k << row_shift) + lane_base in one VALU instruction (k is wave-uniform).
-// lane_base points at tile row 0; row -1, right in front of it, holds zeros.
+// This lane's R rows of tile row k, k being the smallest member of `set`, which is removed from the set: find-first-set
+// and clear-bit on the scalar unit, then address = (k << row_shift) + lane_base in one VALU instruction.  lane_base
+// points at tile row 0.  The empty set yields k = -1 and stays empty (the bit cleared is then bit 63): row -1, right in
+// front of the tile, holds zeros.
 template <int R>
-__device__ __forceinline__ typename RowVec<R>::type tile_row(const char *tile, int lane_base, int k)
+__device__ __forceinline__ typename RowVec<R>::type next_row(const char *tile, int lane_base, u64 &set)
 {
-    int off;
-    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(off) : "s"(k), "n"(row_shift<R>()), "v"(lane_base));
+    int k, off;
+    asm("s_ff1_i32_b64 %1, %0\n\ts_bitset0_b64 %0, %1\n\tv_lshl_add_u32 %2, %1, %3, %4"
+        : "+s"(set), "=&s"(k), "=v"(off)
+        : "n"(row_shift<R>()), "v"(lane_base));
     return *reinterpret_cast<const typename RowVec<R>::type *>(tile + off);
 }
 
 // acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it); when the set has
 // fewer members the rest of the group gathers the row of zeros.  All gathers are issued before the first addition, so
-// COUNT LDS reads are in flight at once.
+// COUNT LDS reads are in flight at once; the additions take the values in pairs (second of a pair first), which
+// halves the number of waits.
 template <int R, bool NEG, int COUNT>
 __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile, int lane_base, u64 &set)
 {
     typedef typename RowVec<R>::type V;
+    static_assert(COUNT % 2 == 0, "pairs");
     V v[COUNT];
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = tile_row<R>(tile, lane_base, pop_lowest(set));
+    for (int i = 0; i < COUNT; ++i) v[i] = next_row<R>(tile, lane_base, set);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < COUNT; ++i) {
-        if constexpr (NEG) acc -= v[i]; else acc += v[i];
+    for (int i = 0; i < COUNT; i += 2) {
+        if constexpr (NEG) { acc -= v[i + 1]; acc -= v[i]; } else { acc += v[i + 1]; acc += v[i]; }
     }
 }
 
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
-// in groups of 8 and, if five or more members are left over, one more group of 8, else a group of 4.  The set is
-// wave-uniform.
+// in groups of 8 and one last group of 6, 4 or 2 (7 or 8 left over: 8), i.e. with at most one gather of the row of
+// zeros per list.  The set is wave-uniform.
 template <int R, bool NEG>
 __device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile, int lane_base)
 {
     int n = members(set);
-    while (n > 4) {
+    while (n >= 7) {
         gather<R, NEG, 8>(acc, tile, lane_base, set);
         n -= 8;
     }
-    if (n > 0) gather<R, NEG, 4>(acc, tile, lane_base, set);
+    if (n >= 5) gather<R, NEG, 6>(acc, tile, lane_base, set);
+    else if (n >= 3) gather<R, NEG, 4>(acc, tile, lane_base, set);
+    else if (n >= 1) gather<R, NEG, 2>(acc, tile, lane_base, set);
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -171,8 +169,8 @@ struct LargeArgs {
     const u64 *masks;
     const float *b;
     float *Y;
-    float *partials;   // [k_slices][rows_pad][n_pad] when k_slices > 1
-    int M, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice, rows_pad;
+    float *partials;   // [tile][k_slices][16 NCW columns][TM rows] when k_slices > 1
+    int M, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
     int remap;   // workgroups per XCD when the grid is spread evenly over the 8 XCDs, else 0
 };
 
@@ -260,70 +258,102 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         }
     }
 
-    // ---- output: Y = acc + b (bias added once, last), or this K slice's partial sums for k_reduce
-    const bool partial = a.k_slices > 1;
-    float *out = partial ? a.partials + (size_t)slice * a.rows_pad * a.n_pad : a.Y;
-    const int ld = partial ? a.n_pad : N;          // row stride
-    const int m_end = partial ? a.rows_pad : M;    // the partial buffers have whole tiles and padded columns
-    const int n_end = partial ? a.n_pad : N;
+    // ---- this K slice's partial sums for k_reduce: the tile as it sits in the registers, [column][row], so that a
+    // wavefront stores 64 R contiguous floats per column
+    if (a.k_slices > 1) {
+        constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
+        float *dst = a.partials + ((size_t)(mt * a.n_colgroups + cg) * a.k_slices + slice) * kTileFloats +
+                     (size_t)(wave * NCW) * TM + lane * R;
+#pragma unroll
+        for (int j = 0; j < NCW; ++j) *reinterpret_cast<V *>(dst + (size_t)j * TM) = acc[j];
+        return;
+    }
+
+    // ---- output: Y = acc + b, bias added once, last
     float bias[NCW];
 #pragma unroll
-    for (int j = 0; j < NCW; ++j) bias[j] = (!partial && a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
-    const bool store_vec =
-        NCW == 4 && (ld % 4 == 0) && (c0 + 4 <= n_end) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
+    for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
+    const bool store_vec = NCW == 4 && (N % 4 == 0) && (c0 + 4 <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int m = m0 + lane * R + r;
-        if (m >= m_end) continue;
-        float *yrow = out + (size_t)m * ld + c0;
+        if (m >= M) continue;
+        float *yrow = a.Y + (size_t)m * N + c0;
         if constexpr (NCW == 4) {
             if (store_vec) {
                 float4v o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = partial ? lane_of<R>(acc[j], r) : lane_of<R>(acc[j], r) + bias[j];
+                for (int j = 0; j < 4; ++j) o[j] = lane_of<R>(acc[j], r) + bias[j];
                 *reinterpret_cast<float4v *>(yrow) = o;
                 continue;
             }
         }
 #pragma unroll
         for (int j = 0; j < NCW; ++j)
-            if (c0 + j < n_end) yrow[j] = partial ? lane_of<R>(acc[j], r) : lane_of<R>(acc[j], r) + bias[j];
+            if (c0 + j < N) yrow[j] = lane_of<R>(acc[j], r) + bias[j];
     }
 }
 
 // ------------------------------------------------------------------------------------------------------------------
-// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b.  One thread per four consecutive columns of a row.
+// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b.  The partial sums of a workgroup tile are stored
+// [column][row]; one workgroup of k_reduce takes 64 rows x C columns of a tile, adds the slices, turns the block
+// round in the LDS and stores rows of Y.  C = 16 NCW columns, TM rows per tile.
 constexpr int kReduceThreads = 256;
 constexpr int kMaxSlices = 8;
 
+template <int C>
 __global__ void __launch_bounds__(kReduceThreads)
-k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__restrict__ Y, int M, int N, int n_pad,
-         int rows_pad, int k_slices, int vec_store)
+k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__restrict__ Y, int M, int N, int n_colgroups,
+         int k_slices, int TM)
 {
-    const int quads = n_pad / 4;
-    const long long id = (long long)blockIdx.x * kReduceThreads + threadIdx.x;
-    const int m = (int)(id / quads), c = (int)(id % quads) * 4;
-    if (m >= M || c >= N) return;
-    const size_t slice_floats = (size_t)rows_pad * n_pad;
-    const float *src = P + (size_t)m * n_pad + c;
-    // all slices are requested before the first addition; the additions then run in slice order
-    float4v part[kMaxSlices];
+    __shared__ float t[C][65];
+    const int sub_per_tile = TM / 64;
+    const int group = blockIdx.x / sub_per_tile, sub = blockIdx.x % sub_per_tile;
+    const int mt = group / n_colgroups, cg = group % n_colgroups;
+    const size_t tile_floats = (size_t)C * TM;
+    const float *base = P + (size_t)group * k_slices * tile_floats + (size_t)sub * 64;
+    const int rr = (threadIdx.x & 15) * 4;
 #pragma unroll
-    for (int s = 0; s < kMaxSlices; ++s)
-        part[s] = *reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * slice_floats);
-    float4v sum = {0.f, 0.f, 0.f, 0.f};
+    for (int pass = 0; pass < C / 16; ++pass) {
+        const int c = pass * 16 + (threadIdx.x >> 4);
+        const float *src = base + (size_t)c * TM + rr;
+        // all slices are requested before the first addition; the additions then run in slice order
+        float4v part[kMaxSlices];
 #pragma unroll
-    for (int s = 0; s < kMaxSlices; ++s)
-        if (s < k_slices) sum += part[s];
-    float *dst = Y + (size_t)m * N + c;
-    if (vec_store && c + 4 <= N) {
-        float4v bias = {0.f, 0.f, 0.f, 0.f};
-        if (b) bias = *reinterpret_cast<const float4v *>(b + c);
-        *reinterpret_cast<float4v *>(dst) = sum + bias;
-    } else {
+        for (int s = 0; s < kMaxSlices; ++s)
+            part[s] = *reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * tile_floats);
+        float4v sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (c + j < N) dst[j] = sum[j] + (b ? b[c + j] : 0.f);
+        for (int s = 0; s < kMaxSlices; ++s)
+            if (s < k_slices) sum += part[s];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[c][rr + i] = sum[i];
+    }
+    __syncthreads();
+    constexpr int kQuads = C / 4;                          // float4 pieces of an output row
+    constexpr int kRowsPerPass = kReduceThreads / kQuads;
+    const int q = threadIdx.x % kQuads;
+    const int n = cg * C + 4 * q;
+    const bool vec = (N % 4 == 0) && (n + 4 <= N) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+    float bias[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bias[j] = (b != nullptr && n + j < N) ? b[n + j] : 0.f;
+#pragma unroll
+    for (int pass = 0; pass < 64 / kRowsPerPass; ++pass) {
+        const int r = pass * kRowsPerPass + threadIdx.x / kQuads;
+        const int m = mt * TM + sub * 64 + r;
+        if (m >= M) continue;
+        float *dst = Y + (size_t)m * N + n;
+        if (vec) {
+            float4v o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = t[4 * q + j][r] + bias[j];
+            *reinterpret_cast<float4v *>(dst) = o;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (n + j < N) dst[j] = t[4 * q + j][r] + bias[j];
+        }
     }
 }
 
@@ -367,26 +397,21 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
     a.partials = d.partials;
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
-    a.rows_pad = (int)(m_tiles * TM);
     const long long groups = m_tiles * a.n_colgroups;
     if (k_slices > kMaxSlices) k_slices = kMaxSlices;
-    const size_t slice_bytes = (size_t)a.rows_pad * l.n_pad * sizeof(float);
+    const size_t slice_bytes = (size_t)groups * NW * NCW * TM * sizeof(float);
     if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
     const long long grid = groups * k_slices;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid > 0x7fffffffLL || groups * (TM / 64) > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess || k_slices == 1) return e;
-
-    const long long quads = (long long)rows * (l.n_pad / 4);
-    const int vec_store = (l.N % 4 == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0) &&
-                          (b == nullptr || (reinterpret_cast<uintptr_t>(b) & 15) == 0);
-    hipLaunchKernelGGL(k_reduce, dim3((unsigned)((quads + kReduceThreads - 1) / kReduceThreads)), dim3(kReduceThreads), 0,
-                       stream, d.partials, b, Y, rows, l.N, l.n_pad, a.rows_pad, k_slices, vec_store);
+    hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / 64))), dim3(kReduceThreads), 0, stream,
+                       d.partials, b, Y, rows, l.N, a.n_colgroups, k_slices, TM);
     return hipGetLastError();
 }
 
