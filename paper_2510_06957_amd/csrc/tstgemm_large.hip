@@ -114,9 +114,10 @@ __device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set,
         gather<R, NEG, 8>(acc, tile, lane_base, set);
         n -= 8;
     }
+    // n is now in [-1, 6]; independent tests instead of an else-chain keep the accumulators in place
     if (n >= 5) gather<R, NEG, 6>(acc, tile, lane_base, set);
-    else if (n >= 3) gather<R, NEG, 4>(acc, tile, lane_base, set);
-    else if (n >= 1) gather<R, NEG, 2>(acc, tile, lane_base, set);
+    if (n == 3 || n == 4) gather<R, NEG, 4>(acc, tile, lane_base, set);
+    if (n == 1 || n == 2) gather<R, NEG, 2>(acc, tile, lane_base, set);
 }
 
 // ------------------------------------------------------------------------------------------------------------------
