@@ -70,54 +70,78 @@ __device__ __forceinline__ int members(u64 set)
     return n;
 }
 
-// This lane's R rows of tile row k, k being the smallest member of `set`, which is removed from the set: find-first-set
-// and clear-bit on the scalar unit, then address = (k << row_shift) + lane_base in one VALU instruction.  lane_base
-// points at tile row 0.  The empty set yields k = -1 and stays empty (the bit cleared is then bit 63): row -1, right in
-// front of the tile, holds zeros.
-template <int R>
-__device__ __forceinline__ typename RowVec<R>::type next_row(const char *tile, int lane_base, u64 &set)
+// The read phase of a group: COUNT times { k = smallest member of `set`, removed from the set (find-first-set and
+// clear-bit on the scalar unit); address = (k << row_shift) + lane_base (one VALU instruction); ds_read of this lane's R
+// rows of tile row k }.  lane_base is the LDS address of this lane's part of tile row 0.  The empty set yields k = -1
+// and stays empty (the bit cleared is then bit 63): row -1, right in front of the tile, holds zeros.  One asm statement,
+// so that nothing is scheduled or inserted between the instructions; the address register is reused (an LDS
+// instruction takes its address when it is issued).
+#define TST_READ(i, width) \
+    "s_ff1_i32_b64 %[k], %[set]\n\ts_bitset0_b64 %[set], %[k]\n\tv_lshl_add_u32 %[a], %[k], %[sh], %[base]\n\t" \
+    "ds_read_" width " %[v" #i "], %[a]\n\t"
+#define TST_READ2(i, j, w) TST_READ(i, w) TST_READ(j, w)
+template <int R, int COUNT>
+__device__ __forceinline__ void read_rows(typename RowVec<R>::type (&v)[8], int lane_base, u64 &set)
 {
-    int k, off;
-    asm("s_ff1_i32_b64 %1, %0\n\ts_bitset0_b64 %0, %1\n\tv_lshl_add_u32 %2, %1, %3, %4"
-        : "+s"(set), "=&s"(k), "=v"(off)
-        : "n"(row_shift<R>()), "v"(lane_base));
-    return *reinterpret_cast<const typename RowVec<R>::type *>(tile + off);
+    int k, a;
+#define TST_OPERANDS \
+    : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a), [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), \
+      [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]) \
+    : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory"
+#define TST_GROUP(w) \
+    if constexpr (COUNT == 8) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_READ2(6, 7, w) TST_OPERANDS); \
+    else if constexpr (COUNT == 6) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_OPERANDS); \
+    else if constexpr (COUNT == 4) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_OPERANDS); \
+    else asm volatile(TST_READ2(0, 1, w) TST_OPERANDS);
+    static_assert(COUNT == 8 || COUNT == 6 || COUNT == 4 || COUNT == 2, "group sizes");
+    if constexpr (R == 4) { TST_GROUP("b128") } else if constexpr (R == 2) { TST_GROUP("b64") } else { TST_GROUP("b32") }
+#undef TST_GROUP
+#undef TST_OPERANDS
 }
 
 // acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it); when the set has
 // fewer members the rest of the group gathers the row of zeros.  All gathers are issued before the first addition, so
 // COUNT LDS reads are in flight at once; the additions take the values in pairs (second of a pair first), which
 // halves the number of waits.
+// Values I and I + 1 of a group of COUNT: the reads return in order and value I + 1 has COUNT - 2 - I younger reads
+// behind it.  (s_waitcnt immediate of gfx9: vmcnt and expcnt fields all ones = no wait, lgkmcnt in bits 11:8; the
+// scheduling barriers keep the additions of a pair behind its wait.)
+template <int R, bool NEG, int COUNT, int I>
+__device__ __forceinline__ void add_pair(typename RowVec<R>::type &acc, const typename RowVec<R>::type (&v)[8])
+{
+    __builtin_amdgcn_s_waitcnt(0xC07F | ((COUNT - 2 - I) << 8));
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (NEG) { acc -= v[I + 1]; acc -= v[I]; } else { acc += v[I + 1]; acc += v[I]; }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int R, bool NEG, int COUNT>
-__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, const char *tile, int lane_base, u64 &set)
+__device__ __forceinline__ void gather(typename RowVec<R>::type &acc, int lane_base, u64 &set)
 {
     typedef typename RowVec<R>::type V;
-    static_assert(COUNT % 2 == 0, "pairs");
-    V v[COUNT];
-#pragma unroll
-    for (int i = 0; i < COUNT; ++i) v[i] = next_row<R>(tile, lane_base, set);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < COUNT; i += 2) {
-        if constexpr (NEG) { acc -= v[i + 1]; acc -= v[i]; } else { acc += v[i + 1]; acc += v[i]; }
-    }
+    V v[8];
+    read_rows<R, COUNT>(v, lane_base, set);
+    add_pair<R, NEG, COUNT, 0>(acc, v);
+    if constexpr (COUNT > 2) add_pair<R, NEG, COUNT, 2>(acc, v);
+    if constexpr (COUNT > 4) add_pair<R, NEG, COUNT, 4>(acc, v);
+    if constexpr (COUNT > 6) add_pair<R, NEG, COUNT, 6>(acc, v);
 }
 
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
 // in groups of 8 and one last group of 6, 4 or 2 (7 or 8 left over: 8), i.e. with at most one gather of the row of
 // zeros per list.  The set is wave-uniform.
 template <int R, bool NEG>
-__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, const char *tile, int lane_base)
+__device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, int lane_base)
 {
     int n = members(set);
     while (n >= 7) {
-        gather<R, NEG, 8>(acc, tile, lane_base, set);
+        gather<R, NEG, 8>(acc, lane_base, set);
         n -= 8;
     }
     // n is now in [-1, 6]; independent tests instead of an else-chain keep the accumulators in place
-    if (n >= 5) gather<R, NEG, 6>(acc, tile, lane_base, set);
-    if (n == 3 || n == 4) gather<R, NEG, 4>(acc, tile, lane_base, set);
-    if (n == 1 || n == 2) gather<R, NEG, 2>(acc, tile, lane_base, set);
+    if (n >= 5) gather<R, NEG, 6>(acc, lane_base, set);
+    if (n == 3 || n == 4) gather<R, NEG, 4>(acc, lane_base, set);
+    if (n == 1 || n == 2) gather<R, NEG, 2>(acc, lane_base, set);
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -237,12 +261,13 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         stage_load(kb0);
         stage_store();
         __syncthreads();
-        const int lane_base = RB + lane * (R * 4);
+        // LDS address of this lane's rows in tile row 0 (the asm reads take plain LDS addresses)
+        const int lane_base = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds + RB + lane * (R * 4);
         for (int kb = kb0; kb < kb1; ++kb) {
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], sets[2 * j], lds, lane_base);
-                run_list<R, true>(acc[j], sets[2 * j + 1], lds, lane_base);
+                run_list<R, false>(acc[j], sets[2 * j], lane_base);
+                run_list<R, true>(acc[j], sets[2 * j + 1], lane_base);
             }
             if (kb + 1 == kb1) break;
             // Exchange the tile.  The requests for the next K-block go out before the barrier, into the registers
