@@ -3,10 +3,12 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2]
 
-One step = one tstgemm() call (the whole hot path: X-tile staging, gather-add, K-block carry, bias
-epilogue) on one batch of synthetic input that is already resident in HBM.  The TCSC build and the
-GPU re-blocking pass run once per matrix before the timed region ("at load time", Sec. 3 of the
-paper) and are reported separately in the config object.  Prints ONE JSON line.
+One step = one tstgemm() call (the whole hot path: X packing / tile staging, gather-add, K-block carry,
+split-K reduction, bias epilogue) on one batch of synthetic input that is already resident in HBM.  The
+TCSC build and the GPU re-blocking pass run once per matrix before the timed region ("at load time",
+Sec. 3 of the paper) and are reported separately in the config object.  Prints ONE JSON line.
+
+The warm-up is long on purpose: the GPU needs some tenths of a second of load to reach its full clock.
 """
 from __future__ import annotations
 
@@ -26,30 +28,40 @@ PEAK_LDS_GATHER_TFLOPS = 256 * 256 * 2.4e9 / 4 / 1e12
 PEAK_ALU_ADD_TFLOPS = 157.3 / 2
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per tstgemm() call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (profiles/), each
+# counter scaled by what it reads for a copy kernel of known size; summed over the kernels of a call and over the
+# main kernel alone.  None where no counter run has been made.
+MEASURED_TRAFFIC = {}
+
 
 def cpu_baseline(W, X, b, nnz, budget_s=10.0):
     """The oracle as it stands, on the host cores, on the same workload; repeated for about budget_s."""
     import oracle
     t = oracle.tcsc_build(W)
     M = X.shape[0]
+    rows = None
+    if M * nnz > 4e10:   # keep the sample to seconds: a slice of rows (the cost per row does not depend on M)
+        rows = np.arange(0, M, M // 64, dtype=np.int32)[:64]
     times = []
     used = 0
     t_start = time.perf_counter()
     while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 200):
         t0 = time.perf_counter()
-        _, _, used = oracle.tstgemm(X, t, b)
+        _, _, used = oracle.tstgemm(X, t, b) if rows is None else oracle.tstgemm(X, t, b, rows=rows)
         times.append(time.perf_counter() - t0)
     mean = float(np.mean(times))
-    return {"value": M * nnz / mean / 1e9, "unit": "Gadds/s", "cores": int(used), "kind": "oracle",
-            "sample": f"whole workload (all {M} rows), {len(times)} repetitions, mean; best "
-                      f"{M * nnz / min(times) / 1e9:.2f} Gadds/s", "ms": mean * 1e3}
+    m_used = M if rows is None else len(rows)
+    return {"value": m_used * nnz / mean / 1e9, "unit": "Gadds/s", "cores": int(used), "kind": "oracle",
+            "sample": (f"whole workload (all {M} rows)" if rows is None else f"{m_used} of {M} rows, evenly spaced")
+                      + f", {len(times)} repetitions, mean; best {m_used * nnz / min(times) / 1e9:.2f} Gadds/s",
+            "ms": mean * 1e3}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5000)
-    ap.add_argument("--warmup", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -78,47 +90,71 @@ def main():
     upload_ms = (time.perf_counter() - t0) * 1e3
     nnz = t.nnz
     lay = tg.tcsc_layout(t)
+    adds = wl.M * nnz
+    # defaults: about 0.2 s of warm-up and 0.5 s of timed work for the headline workload, fewer steps for big ones
+    est_ms = max(adds / 20e12 * 1e3, 0.01)
+    steps = args.steps if args.steps is not None else int(min(5000, max(20, 500.0 / est_ms)))
+    warmup = args.warmup if args.warmup is not None else int(min(2000, max(5, 200.0 / est_ms)))
 
     Xd = torch.from_numpy(X).cuda()
     bd = torch.from_numpy(b).cuda()
     Yd = torch.empty((wl.M, wl.N), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         tg.tstgemm(Xd, t, bd, Yd, stream)
     torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
-    for _ in range(args.steps):
+    for _ in range(steps):
         tg.tstgemm(Xd, t, bd, Yd, stream)
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    kernel_ms = ev0.elapsed_time(ev1) / args.steps      # HIP events on the launch stream
+    ms_per_step = wall * 1e3 / steps
+    call_ms = ev0.elapsed_time(ev1) / steps      # HIP events on the launch stream around all K calls
 
-    adds = wl.M * nnz
+    # The dominant kernel alone: the library records a pair of HIP events around its launch, on the launch stream,
+    # in every call of a second, equally long run (back to back as before, so the clocks stay up).
+    n_k = min(steps, 1000)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_k)]
+    for a, c in pairs:
+        a.record(stream)
+        c.record(stream)
+    torch.cuda.synchronize()
+    for a, c in pairs:
+        tg.tstgemm_profile_events(a, c)
+        tg.tstgemm(Xd, t, bd, Yd, stream)
+    tg.tstgemm_profile_events(None, None)
+    torch.cuda.synchronize()
+    kernel_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
+
     decode = wl.M <= 8
+    traffic = MEASURED_TRAFFIC.get(wl.name)
     if decode:
         # small-M path streams the four TCSC arrays once: index-bandwidth bound
         alg_bytes = 4 * nnz + 8 * (wl.N + 1) + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
         roof = {"bound": "hbm", "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                "unit": "GB/s", "traffic": None}
+                "unit": "GB/s", "traffic": traffic}
     else:
+        # index data the kernel reads (64-bit row sets) + X + Y + b
+        alg_bytes = 16 * lay.n_kblocks * lay.n_pad + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
         roof = {"bound": "lds", "achieved": adds / (kernel_ms * 1e-3) / 1e12, "peak": PEAK_LDS_GATHER_TFLOPS,
-                "unit": "TFLOP/s", "traffic": None,
-                "note": "1 flop = 1 fp32 add = one 4-byte LDS gather; peak = LDS read port 256 B/clk/CU",
+                "unit": "TFLOP/s", "traffic": traffic,
+                "note": "1 flop = 1 fp32 add = one 4-byte LDS gather; peak = LDS read port, 256 B/clk/CU x 256 CUs x "
+                        "2.4 GHz; the fp32 add rate of the vector ALUs (alu_add_peak) is twice that",
                 "alu_add_peak": PEAK_ALU_ADD_TFLOPS}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["kernel"] = "k_decode" if decode else "k_large"
     roof["kernel_ms"] = kernel_ms
     roof["algorithmic_adds_per_launch"] = adds
-    # index data the kernel reads (64-bit row sets / TCSC arrays) + X + Y + b
-    roof["algorithmic_bytes_per_launch"] = (16 * lay.n_kblocks * lay.n_pad if not decode
-                                            else 4 * nnz + 8 * (wl.N + 1)) \
-        + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
+    roof["algorithmic_bytes_per_launch"] = alg_bytes
+    # the same accounting for the whole call (packing pre-pass + main kernel + split-K reduction)
+    roof["call_ms"] = call_ms
+    roof["call_frac"] = (alg_bytes / (call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if decode
+                         else adds / (call_ms * 1e-3) / 1e12 / PEAK_LDS_GATHER_TFLOPS)
     if not decode:
         roof["alu_frac"] = roof["achieved"] / PEAK_ALU_ADD_TFLOPS
 
@@ -126,10 +162,11 @@ def main():
         "metric": "effective Gadds/s (M*nnz(W)), fp32 X, sparse ternary GEMM Y = XW + b",
         "value": adds / (ms_per_step * 1e-3) / 1e9,
         "unit": "Gadds/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: M={wl.M} K={wl.K} N={wl.N} density={wl.density} X,b~{wl.dist} "
-                               f"seed={wl.seed}", "nnz": nnz, "index_type": "int32 TCSC in, 64-bit row sets per K-block on device",
+                               f"seed={wl.seed}", "nnz": nnz,
+                   "index_type": "int32 TCSC in, 64-bit row sets per K-block on device",
                    "tcsc_build_ms_host": build_ms, "upload_and_reblock_ms": upload_ms},
         "roofline": roof,
     }

@@ -4,8 +4,8 @@
  * C ABI of libtstgemm.so.  Plain pointers and sizes only; every pointer argument says
  * whether it is HOST or DEVICE memory.  All functions return 0 (TSTGEMM_OK) or a negative
  * TSTGEMM_E* code; tcsc_strerror() turns a code into text.  No function throws, aborts or
- * prints.  Besides what a handle owns the library keeps one piece of global state, the tuning
- * overrides of tstgemm_set_tuning().
+ * prints.  Besides what a handle owns the library keeps two pieces of global state: the tuning
+ * overrides of tstgemm_set_tuning() and the event pair of tstgemm_profile_events().
  *
  * The operation is Eq. 1 of the paper (Sec. 2): X is dense fp32 (M x K, row-major), W is a
  * K x N matrix with entries in {-1, 0, +1}, b (N) is added to every row of the product,
@@ -81,8 +81,9 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *
  *   masks      uint64 [n_kblocks][n_pad][2]   [kb][n][0]: the +1 rows of column n inside K-block
  *                                             kb, [kb][n][1]: the -1 rows
- *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): arrival counters, split-K partial sums and a
- *                                             transposed copy of (a slab of rows of) X
+ *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): split-K partial sums (32 MiB) and a tiled,
+ *                                             transposed copy of (a slab of rows of) X (128 MiB, or one tile of
+ *                                             256 rows over the padded K if that is larger)
  * n_pad = N rounded up to a multiple of 64; columns >= N have empty sets.
  */
 typedef struct tcsc_layout {
@@ -121,12 +122,23 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
- * Launch-shape overrides for the large-M kernel, for tuning runs: columns per wavefront
- * (1, 2 or 4) and number of K slices (1..8) computed by different workgroups and summed in a
- * fixed order.  0 restores the built-in choice for that parameter.  Process-wide.
+ * Launch-shape overrides for the large-M path, for tuning runs and tests: columns per wavefront
+ * (1, 2 or 4), number of K slices (1..8) computed by different workgroups and summed in a
+ * fixed order, and the largest number of row tiles of X packed and processed at a time
+ * (>= 1).  0 restores the built-in choice for that parameter.  Process-wide.
  * Errors: EINVAL for a value outside the ranges above.
  */
-int tstgemm_set_tuning(int cols_per_wave, int k_slices);
+int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
+
+/*
+ * For benchmarks that must time one kernel: from now on every tstgemm() call records the
+ * hipEvent_t `before` right before and `after` right after the launch of its main kernel
+ * (the gather-add kernel; not the packing pre-pass and the split-K reduction of the large-M
+ * path), on the call's stream.  Both NULL switches this off (the default).  The events are
+ * the caller's; a call with more than one slab of rows records them once per slab, so the pair
+ * then brackets the last slab only.  Process-wide.  Errors: EINVAL if exactly one is NULL.
+ */
+int tstgemm_profile_events(void *before, void *after);
 
 /* Release the handle and its host arrays (not the device buffer).  NULL is allowed. */
 void tcsc_destroy(tcsc_t *t);

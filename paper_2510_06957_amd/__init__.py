@@ -4,9 +4,11 @@ Python binding of libtstgemm.so: argument marshalling only, every step of the co
 runs in the HIP library.  PyTorch supplies device memory and streams.
 """
 from .binding import (TstgemmError, Tcsc, library_path, tcsc_build, tcsc_from_arrays, tcsc_to_dense, tcsc_dims,
-                      tcsc_arrays, tcsc_device_bytes, tcsc_layout, tcsc_upload, tstgemm, tstgemm_set_tuning, tcsc_destroy,
+                      tcsc_arrays, tcsc_device_bytes, tcsc_layout, tcsc_upload, tstgemm, tstgemm_set_tuning, tstgemm_profile_events,
+                      tcsc_destroy,
                       tcsc_strerror)
 
 __all__ = ["TstgemmError", "Tcsc", "library_path", "tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims",
-           "tcsc_arrays", "tcsc_device_bytes", "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tcsc_destroy",
+           "tcsc_arrays", "tcsc_device_bytes", "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tstgemm_profile_events",
+           "tcsc_destroy",
            "tcsc_strerror"]

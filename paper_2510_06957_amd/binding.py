@@ -62,8 +62,10 @@ def _load():
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
     lib.tcsc_strerror.restype = ctypes.c_char_p
-    lib.tstgemm_set_tuning.argtypes = [ci, ci]
+    lib.tstgemm_set_tuning.argtypes = [ci, ci, ci]
     lib.tstgemm_set_tuning.restype = ci
+    lib.tstgemm_profile_events.argtypes = [vp, vp]
+    lib.tstgemm_profile_events.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm"):
         getattr(lib, name).restype = ci
@@ -223,8 +225,15 @@ def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None):
     return Y
 
 
-def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0):
-    _check(_load().tstgemm_set_tuning(int(cols_per_wave), int(k_slices)), "tstgemm_set_tuning")
+def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0, slab_tiles: int = 0):
+    _check(_load().tstgemm_set_tuning(int(cols_per_wave), int(k_slices), int(slab_tiles)), "tstgemm_set_tuning")
+
+
+def tstgemm_profile_events(before=None, after=None):
+    """before / after: torch.cuda.Event(enable_timing=True) objects that have been recorded once (so that their
+    native handles exist), or None for both to switch the recording off."""
+    raw = [None if e is None else ctypes.c_void_p(e.cuda_event) for e in (before, after)]
+    _check(_load().tstgemm_profile_events(*raw), "tstgemm_profile_events")
 
 
 def tcsc_destroy(t: Tcsc):

@@ -217,12 +217,21 @@ int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, in
     return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
 }
 
-int tstgemm_set_tuning(int cols_per_wave, int k_slices)
+int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)
 {
     if (cols_per_wave != 0 && cols_per_wave != 1 && cols_per_wave != 2 && cols_per_wave != 4) return TSTGEMM_EINVAL;
-    if (k_slices < 0 || k_slices > 8) return TSTGEMM_EINVAL;
+    if (k_slices < 0 || k_slices > 8 || slab_tiles < 0) return TSTGEMM_EINVAL;
     tst::g_cols_per_wave = cols_per_wave;
     tst::g_k_slices = k_slices;
+    tst::g_slab_tiles = slab_tiles;
+    return TSTGEMM_OK;
+}
+
+int tstgemm_profile_events(void *before, void *after)
+{
+    if ((before == nullptr) != (after == nullptr)) return TSTGEMM_EINVAL;
+    tst::g_event_before = static_cast<hipEvent_t>(before);
+    tst::g_event_after = static_cast<hipEvent_t>(after);
     return TSTGEMM_OK;
 }
 

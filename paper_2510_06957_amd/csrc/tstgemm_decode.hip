@@ -104,9 +104,13 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, hipSt
     int grid = compute_units() * per_cu;
     const int need = (t->N + kDecodeThreads / 64 - 1) / (kDecodeThreads / 64);
     if (grid > need) grid = need;
+    hipError_t e;
+    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_decode<MM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
                        d.col_start_neg, d.row_index_pos, d.row_index_neg, b, Y, t->K, t->N);
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    return e;
 }
 
 }  // namespace

@@ -62,7 +62,8 @@ inline DeviceTcsc device_view(const tcsc *t)
 hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
 // tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 8.
 hipError_t launch_large(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);
-extern int g_cols_per_wave, g_k_slices;   // tuning overrides, 0 = built-in choice
+extern int g_cols_per_wave, g_k_slices, g_slab_tiles;   // tuning overrides, 0 = built-in choice
+extern hipEvent_t g_event_before, g_event_after;       // recorded around the main kernel of a call when set
 // tstgemm_decode.hip -- small-M kernel (M <= 8, whole X resident in the LDS).
 bool decode_supported(int M, int K);
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);

@@ -36,7 +36,8 @@
 
 namespace tst {
 
-int g_cols_per_wave = 0, g_k_slices = 0;
+int g_cols_per_wave = 0, g_k_slices = 0, g_slab_tiles = 0;
+hipEvent_t g_event_before = nullptr, g_event_after = nullptr;
 
 namespace {
 
@@ -433,8 +434,10 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
     const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL || groups * (TM / 64) > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
+    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
+    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
     hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / 64))), dim3(kReduceThreads), 0, stream,
                        d.partials, b, Y, rows, l.N, a.n_colgroups, k_slices, TM);
@@ -454,6 +457,7 @@ template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, 
     long long slab_rows = (long long)(d.xt_capacity / tile_bytes) * TM;
     if (slab_rows < TM) return hipErrorInvalidValue;
     if (slab_rows > 65535LL * 64) slab_rows = 65535LL * 64 / TM * TM;
+    if (g_slab_tiles > 0 && slab_rows > (long long)g_slab_tiles * TM) slab_rows = (long long)g_slab_tiles * TM;
     for (long long m_begin = 0; m_begin < M; m_begin += slab_rows) {
         const int rows = (int)((M - m_begin) < slab_rows ? (M - m_begin) : slab_rows);
         const long long m_tiles = (rows + TM - 1) / TM;

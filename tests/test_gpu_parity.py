@@ -130,3 +130,65 @@ def test_prefill_config_sampled_rows(name):
     Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, b, rows=rows)
     assert np.array_equal(Yi[rows], Ydi.astype(np.float32))
+
+
+@pytest.mark.parametrize("cols_per_wave", [1, 2, 4])
+@pytest.mark.parametrize("k_slices", [1, 3, 8])
+def test_launch_shapes(cols_per_wave, k_slices):
+    """Every launch shape of the large-M path (columns per wavefront, K slices with the reduction kernel, X packed
+    and processed in slabs of one or two row tiles) gives the same, correct result; integer inputs bit for bit."""
+    M, K, N = 600, 700, 200
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=41)
+    _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=42)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, b)
+    h = None
+    try:
+        for slab_tiles in (0, 1, 2):
+            tg.tstgemm_set_tuning(cols_per_wave, k_slices, slab_tiles)
+            Y, h = gpu_tstgemm(W, X, b, handle=h)
+            assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices} slab={slab_tiles}")
+            Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+            assert np.array_equal(Yi, Ydi.astype(np.float32))
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+
+
+@pytest.mark.parametrize("M,K,N", [(70, 130, 67), (300, 516, 100), (6, 130, 40)])
+def test_unaligned_operands(M, K, N):
+    """X, b and Y that start 4 bytes off a 16-byte boundary (views into larger tensors): the element-wise paths."""
+    import torch
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=43)
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    Xbuf = torch.zeros(M * K + 1, dtype=torch.float32, device="cuda")
+    bbuf = torch.zeros(N + 1, dtype=torch.float32, device="cuda")
+    Ybuf = torch.full((M * N + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    Xd, bd, Yd_ = Xbuf[1:].view(M, K), bbuf[1:], Ybuf[1:].view(M, N)
+    assert Xd.data_ptr() % 16 == 4
+    Xd.copy_(torch.from_numpy(X))
+    bd.copy_(torch.from_numpy(b))
+    tg.tstgemm(Xd, t, bd, Yd_)
+    torch.cuda.synchronize()
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    assert_close(Yd_.cpu().numpy(), Yd, A, f"unaligned {M}x{K}x{N}")
+
+
+def test_profile_events_bracket_the_main_kernel():
+    import torch
+    W, X, b = si.make_workload("C1")
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(b).cuda()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); e1.record()
+    torch.cuda.synchronize()
+    try:
+        tg.tstgemm_profile_events(e0, e1)
+        Y = tg.tstgemm(Xd, t, bd)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+    finally:
+        tg.tstgemm_profile_events(None, None)
+    assert 0.0 < ms < 50.0
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    assert_close(Y.cpu().numpy(), Yd, A, "C1 with events")

@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(str(tg.library_path()))
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tcsc_destroy", "tcsc_strerror"} <= names
+            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tstgemm_profile_events", "tcsc_destroy",
+            "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
 
@@ -117,3 +118,15 @@ def test_layout_bookkeeping():
     assert lay.total_bytes == tg.tcsc_device_bytes(t)
     assert lay.off_workspace - lay.off_masks >= 16 * lay.n_kblocks * lay.n_pad
     assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
+
+
+def test_tuning_rejects_bad_values():
+    lib = ctypes.CDLL(str(tg.library_path()))
+    assert lib.tstgemm_set_tuning(3, 0, 0) == -1
+    assert lib.tstgemm_set_tuning(0, 9, 0) == -1
+    assert lib.tstgemm_set_tuning(0, 0, -1) == -1
+    assert lib.tstgemm_set_tuning(4, 8, 2) == 0
+    assert lib.tstgemm_set_tuning(0, 0, 0) == 0
+    one = ctypes.c_void_p(1)
+    assert lib.tstgemm_profile_events(one, None) == -1
+    assert lib.tstgemm_profile_events(None, None) == 0
