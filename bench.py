@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run a plain 256 MiB copy kernel a few times (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: "
+                         "what the counters read for it gives their scale)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1",
@@ -100,6 +103,14 @@ def main():
     bd = torch.from_numpy(b).cuda()
     Yd = torch.empty((wl.M, wl.N), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
+
+    if args.traffic_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")   # 256 MiB read, 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(warmup):
         tg.tstgemm(Xd, t, bd, Yd, stream)

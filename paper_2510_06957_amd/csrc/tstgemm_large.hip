@@ -292,7 +292,7 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         float *dst = a.partials + ((size_t)(mt * a.n_colgroups + cg) * a.k_slices + slice) * kTileFloats +
                      (size_t)(wave * NCW) * TM + lane * R;
 #pragma unroll
-        for (int j = 0; j < NCW; ++j) *reinterpret_cast<V *>(dst + (size_t)j * TM) = acc[j];
+        for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<V *>(dst + (size_t)j * TM));
         return;
     }
 
@@ -323,9 +323,11 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
 
 // ------------------------------------------------------------------------------------------------------------------
 // k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b.  The partial sums of a workgroup tile are stored
-// [column][row]; one workgroup of k_reduce takes 64 rows x C columns of a tile, adds the slices, turns the block
-// round in the LDS and stores rows of Y.  C = 16 NCW columns, TM rows per tile.
+// [column][row]; one workgroup of k_reduce takes kReduceRows rows x C columns of a tile, adds the slices, turns the
+// block round in the LDS and stores rows of Y.  C = 16 NCW columns, TM rows per tile.  The partial sums are read
+// once and were written past the caches, so they are loaded as non-temporal data.
 constexpr int kReduceThreads = 256;
+constexpr int kReduceRows = 32;
 constexpr int kMaxSlices = 8;
 
 template <int C>
@@ -333,22 +335,27 @@ __global__ void __launch_bounds__(kReduceThreads)
 k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__restrict__ Y, int M, int N, int n_colgroups,
          int k_slices, int TM)
 {
-    __shared__ float t[C][65];
-    const int sub_per_tile = TM / 64;
+    __shared__ float t[C][kReduceRows + 1];
+    constexpr int kRowQuads = kReduceRows / 4;                   // threads along the rows of a column
+    constexpr int kColsPerPass = kReduceThreads / kRowQuads;
+    static_assert(C % kColsPerPass == 0 || kColsPerPass % C == 0, "column passes");
+    const int sub_per_tile = TM / kReduceRows;
     const int group = blockIdx.x / sub_per_tile, sub = blockIdx.x % sub_per_tile;
     const int mt = group / n_colgroups, cg = group % n_colgroups;
     const size_t tile_floats = (size_t)C * TM;
-    const float *base = P + (size_t)group * k_slices * tile_floats + (size_t)sub * 64;
-    const int rr = (threadIdx.x & 15) * 4;
+    const float *base = P + (size_t)group * k_slices * tile_floats + (size_t)sub * kReduceRows;
+    const int rr = (threadIdx.x % kRowQuads) * 4;
 #pragma unroll
-    for (int pass = 0; pass < C / 16; ++pass) {
-        const int c = pass * 16 + (threadIdx.x >> 4);
+    for (int pass = 0; pass < (C + kColsPerPass - 1) / kColsPerPass; ++pass) {
+        const int c = pass * kColsPerPass + threadIdx.x / kRowQuads;
+        if (C < kColsPerPass && c >= C) break;
         const float *src = base + (size_t)c * TM + rr;
         // all slices are requested before the first addition; the additions then run in slice order
         float4v part[kMaxSlices];
 #pragma unroll
         for (int s = 0; s < kMaxSlices; ++s)
-            part[s] = *reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * tile_floats);
+            part[s] = __builtin_nontemporal_load(
+                reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * tile_floats));
         float4v sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < kMaxSlices; ++s)
@@ -366,10 +373,10 @@ k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__rest
 #pragma unroll
     for (int j = 0; j < 4; ++j) bias[j] = (b != nullptr && n + j < N) ? b[n + j] : 0.f;
 #pragma unroll
-    for (int pass = 0; pass < 64 / kRowsPerPass; ++pass) {
+    for (int pass = 0; pass < (kReduceRows + kRowsPerPass - 1) / kRowsPerPass; ++pass) {
         const int r = pass * kRowsPerPass + threadIdx.x / kQuads;
-        const int m = mt * TM + sub * 64 + r;
-        if (m >= M) continue;
+        const int m = mt * TM + sub * kReduceRows + r;
+        if (r >= kReduceRows || m >= M) continue;
         float *dst = Y + (size_t)m * N + n;
         if (vec) {
             float4v o;
@@ -432,14 +439,14 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
     const long long grid = groups * k_slices;
-    if (grid > 0x7fffffffLL || groups * (TM / 64) > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid > 0x7fffffffLL || groups * (TM / kReduceRows) > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
-    hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / 64))), dim3(kReduceThreads), 0, stream,
+    hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / kReduceRows))), dim3(kReduceThreads), 0, stream,
                        d.partials, b, Y, rows, l.N, a.n_colgroups, k_slices, TM);
     return hipGetLastError();
 }
