@@ -28,10 +28,10 @@ PEAK_LDS_GATHER_TFLOPS = 256 * 256 * 2.4e9 / 4 / 1e12
 PEAK_ALU_ADD_TFLOPS = 157.3 / 2
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per tstgemm() call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (profiles/), each
-# counter scaled by what it reads for a copy kernel of known size; summed over the kernels of a call and over the
-# main kernel alone.  None where no counter run has been made.
-MEASURED_TRAFFIC = {}
+# HBM bytes of one launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
+# (profiles/tstgemm_C2_hbm_traffic.md), each counter scaled by what it reads for a copy kernel of known size in the
+# same run.  None where no counter run has been made.
+MEASURED_TRAFFIC = {"C2": (12448 + 32768) * 1024}
 
 
 def cpu_baseline(W, X, b, nnz, budget_s=10.0):

@@ -20,8 +20,8 @@
 //     the scalar unit; the scalar unit turns it into row numbers with find-first-set /
 //     clear-bit, so an index costs two SALU instructions and neither VALU work, LDS traffic nor
 //     memory latency.  An exhausted set yields row -1, the row of zeros: pieces are padded to
-//     a multiple of four gathers that way (the paper pads its interleaved groups with a dummy
-//     zero index for the same reason, Sec. 3), which leaves only two group sizes, 8 and 4;
+//     an even number of gathers that way (the paper pads its interleaved groups with a dummy
+//     zero index for the same reason, Sec. 3), which leaves four group sizes: 8, 6, 4 and 2;
 //   * the gathers of a group are all issued before the first addition; the latency of a group
 //     is covered by the other wavefronts: the kernel is built for 8 wavefronts per SIMD (at
 //     most 64 VGPRs, two workgroups per compute unit).  While one workgroup exchanges its tile
@@ -30,8 +30,8 @@
 //     the store are fused;
 //   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
 //     8 slices handled by different workgroups; each writes its partial sums to the workspace,
-//     and k_reduce adds the slices in slice order, adds the bias and stores Y -- a fixed
-//     summation order, so results do not depend on timing, and no atomics or fences.
+//     past the caches, and k_reduce adds the slices in slice order, adds the bias and stores Y
+//     -- a fixed summation order, so results do not depend on timing, and no atomics or fences.
 #include "tstgemm_internal.h"
 
 namespace tst {
