@@ -83,7 +83,22 @@ def make_inputs(M: int, K: int, N: int, density: float, dist: str, seed: int):
     return W, X, b
 
 
+def workload(name: str) -> Workload:
+    """A benchmark configuration by name, or an ad-hoc one spelled "M<m>-K<k>-N<n>-d<density>" (uniform X and b,
+    seed derived from the shape): the shapes of the paper's own sweeps (Sec. 4) are named that way."""
+    if name in WORKLOADS:
+        return WORKLOADS[name]
+    try:
+        parts = dict((p[0], p[1:]) for p in name.split("-"))
+        M, K, N, d = int(parts["M"]), int(parts["K"]), int(parts["N"]), float(parts["d"])
+    except (KeyError, ValueError, IndexError):
+        raise KeyError(f"unknown workload {name!r}") from None
+    if min(M, K, N) < 1 or not 0.0 <= d <= 1.0:
+        raise KeyError(f"bad workload {name!r}")
+    return Workload(name, M, K, N, d, "uniform", 2000 + (M * 31 + K * 17 + N * 7 + int(d * 4096)) % 100000)
+
+
 def make_workload(name: str, dist: str | None = None, M: int | None = None):
     """Inputs of a named workload; `dist` / `M` override the distribution / row count."""
-    w = WORKLOADS[name]
+    w = workload(name)
     return make_inputs(M if M is not None else w.M, w.K, w.N, w.density, dist or w.dist, w.seed)
