@@ -159,22 +159,26 @@ k_pack_x(const float *__restrict__ X, float *__restrict__ xt, int rows, int K, i
     const int kb = blockIdx.x, m0 = blockIdx.y * 64;
     const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
     const int k = kb * 64 + 4 * c;
+    // The four loads are issued unconditionally, so that they are all in flight together: rows beyond the last one
+    // read the last row, pieces beyond K read the start of the row, and both are zeroed afterwards.
+    float4v v[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const int row = r + 16 * p, m = m0 + row;
-        float4v v = {0.f, 0.f, 0.f, 0.f};
-        if (m < rows) {
-            const float *src = X + (size_t)m * K + k;
-            if constexpr (VEC) {
-                if (k < K) v = *reinterpret_cast<const float4v *>(src);
-            } else {
+        const int m = m0 + r + 16 * p;
+        const float *src = X + (size_t)min(m, rows - 1) * K;
+        if constexpr (VEC) {
+            v[p] = *reinterpret_cast<const float4v *>(src + (k < K ? k : 0));   // K % 4 == 0: inside or outside as a whole
+        } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (k + j < K) v[j] = src[j];
-            }
+            for (int j = 0; j < 4; ++j) v[p][j] = src[k + j < K ? k + j : 0];
         }
+    }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t[4 * c + j][row] = v[j];
+    for (int p = 0; p < 4; ++p) {
+        const int row = r + 16 * p;
+        const bool row_ok = m0 + row < rows;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t[4 * c + j][row] = (row_ok && k + j < K) ? v[p][j] : 0.f;
     }
     __syncthreads();
     const int kk = threadIdx.x >> 2, q = threadIdx.x & 3;
