@@ -26,6 +26,7 @@ def _load():
         lib.oracle_tcsc_build.restype = ctypes.c_int
         lib.oracle_tcsc_count.restype = ctypes.c_int
         lib.oracle_tcsc_to_dense.restype = ctypes.c_int
+        lib.oracle_prelu.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -122,4 +123,20 @@ def tstgemm_points(X: np.ndarray, t: Tcsc, b: np.ndarray | None, ms, ns):
                                        M, K, t.N, _p(Yd), _p(A))
     if rc:
         raise ValueError(f"oracle_tstgemm_points failed ({rc})")
+    return Yd, A
+
+
+def prelu(Yd: np.ndarray, A: np.ndarray | None, alpha) -> tuple[np.ndarray, np.ndarray | None]:
+    """PReLU of a finished Y (rows x N, float64): copies of (Yd, A) with v <= 0 replaced by alpha * v and the
+    tolerance scale multiplied by max(1, |alpha|).  alpha: one slope, or one per column."""
+    Yd = np.array(Yd, dtype=np.float64, order="C", copy=True)
+    if Yd.ndim != 2:
+        raise ValueError("Yd must be a matrix")
+    A = None if A is None else np.array(A, dtype=np.float64, order="C", copy=True)
+    alpha = np.ascontiguousarray(np.atleast_1d(alpha), dtype=np.float32)
+    if alpha.size not in (1, Yd.shape[1]):
+        raise ValueError("alpha must have 1 or N entries")
+    rc = _load().oracle_prelu(_p(Yd), _p(A), Yd.shape[0], Yd.shape[1], _p(alpha), int(alpha.size))
+    if rc:
+        raise ValueError(f"oracle_prelu failed ({rc})")
     return Yd, A

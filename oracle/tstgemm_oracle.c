@@ -26,6 +26,12 @@
  *   A[m][n] = sum over the selected entries of |X[m][k]|  +  |b[n]|,
  * the magnitude the parity tolerance is scaled by.
  *
+ * Optional activation (the paper fuses PReLU into its vectorised kernels, Sec. 2
+ * "Implementation Note" and Sec. 4, without stating its formula or slope): oracle_prelu
+ * applies the usual definition  PReLU(v) = v for v > 0, alpha * v otherwise  to a finished
+ * Y, with one slope for all outputs or one per column of Y (output channel); the slopes are
+ * inputs.  This is the only multiplication anywhere in the oracle.
+ *
  * Parity pins (tests, CPU only): a hand-worked example, dense brute force through a
  * library matrix product on small and odd shapes, a sparse-library CSC construction for
  * the format, and the invariants W=0 => Y=b, Y(-W)-b = -(Y(W)-b), row permutation,
@@ -168,5 +174,25 @@ int oracle_tstgemm_points(const float *X,
     for (int64_t i = 0; i < n_points; ++i)
         oracle_element(X + (size_t)ms[i] * K, col_start_pos, col_start_neg, row_index_pos, row_index_neg,
                        b, ns[i], &Yd[i], A ? &A[i] : 0);
+    return ORACLE_OK;
+}
+
+/*
+ * PReLU on a finished block of Y (n_rows x N, row-major, in place): v > 0 stays, otherwise
+ * v becomes alpha * v.  alpha_count == 1: alpha[0] for every output; alpha_count == N: alpha[n]
+ * for column n.  A (may be NULL) is scaled by max(1, |alpha|): the function is Lipschitz with
+ * that constant, so an error bound on v carries over with this factor.
+ */
+int oracle_prelu(double *Yd, double *A, int n_rows, int N, const float *alpha, int alpha_count)
+{
+    if (!Yd || !alpha || n_rows < 0 || N < 0 || (alpha_count != 1 && alpha_count != N)) return ORACLE_BAD_ARG;
+    for (int r = 0; r < n_rows; ++r) {
+        for (int n = 0; n < N; ++n) {
+            double a = (double)alpha[alpha_count == 1 ? 0 : n];
+            double v = Yd[(size_t)r * N + n];
+            if (!(v > 0.0)) Yd[(size_t)r * N + n] = a * v;
+            if (A && fabs(a) > 1.0) A[(size_t)r * N + n] *= fabs(a);
+        }
+    }
     return ORACLE_OK;
 }

@@ -174,3 +174,38 @@ def test_generator_statistics():
     assert X.min() >= -1 and X.max() < 1
     W2, X2, b2 = si.make_inputs(4, K, N, d, "uniform", seed=1002)
     assert np.array_equal(W, W2) and np.array_equal(X, X2) and np.array_equal(b, b2)
+
+
+def test_prelu_worked_example(golden_dir):
+    g = json.loads((golden_dir / "worked_example.json").read_text())
+    t = oracle.tcsc_build(np.array(g["W"], np.int8))
+    Yd, A, _ = oracle.tstgemm(np.array(g["X"], np.float32), t, np.array(g["b"], np.float32))
+    Yp, Ap = oracle.prelu(Yd, A, g["alpha_per_column"])
+    assert Yp.tolist() == g["Y_prelu_per_column"]
+    assert Ap.tolist() == (np.array(g["A"]) * np.maximum(1.0, np.abs(g["alpha_per_column"]))).tolist()
+    Ys, As = oracle.prelu(Yd, A, g["alpha_scalar"])
+    assert Ys.tolist() == g["Y_prelu_scalar"]
+    assert As.tolist() == g["A"]
+
+
+def test_prelu_special_slopes_and_library():
+    """Slope 1 is the identity, slope 0 is max(v, 0), slope -1 is |v|; arbitrary per-column slopes against torch's
+    CPU prelu in float64."""
+    import torch
+    W, X, b = si.make_inputs(6, 70, 9, 0.5, "normal", seed=55)
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    assert (Yd < 0).any() and (Yd > 0).any()
+    assert np.array_equal(oracle.prelu(Yd, A, 1.0)[0], Yd)
+    assert np.array_equal(oracle.prelu(Yd, A, 0.0)[0], np.maximum(Yd, 0.0))
+    assert np.array_equal(oracle.prelu(Yd, A, -1.0)[0], np.abs(Yd))
+    alpha = np.linspace(-2.0, 3.0, 9).astype(np.float32)
+    Yp, Ap = oracle.prelu(Yd, A, alpha)
+    ref = torch.nn.functional.prelu(torch.from_numpy(Yd), torch.from_numpy(alpha.astype(np.float64))).numpy()
+    assert np.array_equal(Yp, ref)
+    assert np.array_equal(Ap, A * np.maximum(1.0, np.abs(alpha.astype(np.float64))))
+    same = np.full(9, 0.3, np.float32)
+    assert np.array_equal(oracle.prelu(Yd, A, same)[0], oracle.prelu(Yd, A, np.float32(0.3))[0])
+    # the inputs are left alone
+    Y0 = Yd.copy()
+    oracle.prelu(Yd, A, alpha)
+    assert np.array_equal(Yd, Y0)
