@@ -123,6 +123,19 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
+ * Y = PReLU(X W + b): tstgemm() with the activation fused behind the bias add.  The paper fuses
+ * PReLU into its vectorised kernels (Sec. 2 "Implementation Note", Sec. 4) without giving the
+ * formula or the slope; here it is the usual one, PReLU(v) = v for v > 0 and alpha * v otherwise,
+ * and the slopes are an input.
+ * alpha: DEVICE fp32, alpha_count entries: 1 (one slope for all outputs) or N (alpha[n] for
+ * column n of Y).  Everything else as for tstgemm().  The slope multiplication is the only
+ * multiplication of the path; it rounds once in fp32.  Errors: as tstgemm(), and EINVAL for a
+ * NULL alpha or an alpha_count other than 1 or N.
+ */
+int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *alpha, int alpha_count, float *Y,
+                  int M, int K, int N, void *stream);
+
+/*
  * Launch-shape overrides for the large-M path, for tuning runs and tests: columns per wavefront
  * (1, 2 or 4), number of K slices (1..8) computed by different workgroups and summed in a
  * fixed order, and the largest number of row tiles of X packed and processed at a time

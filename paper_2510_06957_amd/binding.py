@@ -58,6 +58,7 @@ def _load():
     lib.tcsc_layout.argtypes = [vp, ctypes.POINTER(TcscLayout)]
     lib.tcsc_upload.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tstgemm.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.tstgemm_prelu.argtypes = [vp, vp, vp, vp, ci, vp, ci, ci, ci, vp]
     lib.tcsc_destroy.argtypes = [vp]
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
@@ -67,7 +68,7 @@ def _load():
     lib.tstgemm_profile_events.argtypes = [vp, vp]
     lib.tstgemm_profile_events.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-                 "tcsc_layout", "tcsc_upload", "tstgemm"):
+                 "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -194,11 +195,12 @@ def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
     return t
 
 
-def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None):
-    """Y = X W + b on the GPU.  X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None.
+def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
+    """Y = X W + b on the GPU, or Y = PReLU(X W + b) when `alpha` is given (tstgemm_prelu of the C ABI).
+    X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None; alpha: cuda float32 with 1 or N entries.
 
     Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
-    handle was uploaded to and the one holding X, b and Y."""
+    handle was uploaded to and the one holding X, b, alpha and Y."""
     import torch
     f32 = torch.float32
     if not (X.is_cuda and X.dtype == f32 and X.dim() == 2 and X.is_contiguous()):
@@ -214,12 +216,19 @@ def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None):
         b_ptr = b.data_ptr()
     else:
         raise ValueError("b must be a contiguous float32 CUDA vector of length N on X's device")
+    if alpha is not None and not (alpha.is_cuda and alpha.dtype == f32 and alpha.is_contiguous()
+                                  and alpha.numel() in (1, N) and alpha.device.index == dev):
+        raise ValueError("alpha must be a contiguous float32 CUDA tensor with 1 or N entries on X's device")
     if Y is None:
         Y = torch.empty((M, N), dtype=f32, device=X.device)
     elif not (Y.is_cuda and Y.dtype == f32 and Y.dim() == 2 and Y.shape[0] == M and Y.shape[1] == N
               and Y.is_contiguous() and Y.device.index == dev):
         raise ValueError("Y must be a contiguous float32 CUDA matrix of shape [M, N] on X's device")
-    rc = _load().tstgemm(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if alpha is None:
+        rc = _load().tstgemm(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    else:
+        rc = _load().tstgemm_prelu(X.data_ptr(), t.handle, b_ptr, alpha.data_ptr(), alpha.numel(), Y.data_ptr(), M, K, N,
+                                   _stream_ptr(stream))
     if rc != 0:
         raise TstgemmError(rc, "tstgemm")
     return Y

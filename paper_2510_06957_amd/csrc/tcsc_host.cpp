@@ -206,15 +206,36 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
     return TSTGEMM_OK;
 }
 
-int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
+}  // extern "C"
+
+namespace {
+
+int run(const float *X, const tcsc_t *t, const float *b, const tst::Activation &act, float *Y, int M, int K, int N,
+        void *stream)
 {
     if (!X || !t || !Y || M < 1) return TSTGEMM_EINVAL;
     if (K != t->K || N != t->N) return TSTGEMM_EINVAL;
     if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, Y, M, s)
-                                               : tst::launch_large(X, t, b, Y, M, s);
+    hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, act, Y, M, s)
+                                               : tst::launch_large(X, t, b, act, Y, M, s);
     return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
+{
+    return run(X, t, b, tst::Activation{nullptr, 0}, Y, M, K, N, stream);
+}
+
+int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *alpha, int alpha_count, float *Y, int M,
+                  int K, int N, void *stream)
+{
+    if (!alpha || (alpha_count != 1 && alpha_count != N)) return TSTGEMM_EINVAL;
+    return run(X, t, b, tst::Activation{alpha, alpha_count == 1 ? 0 : 1}, Y, M, K, N, stream);
 }
 
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)

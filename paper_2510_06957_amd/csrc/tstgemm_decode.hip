@@ -9,7 +9,7 @@
 //     (the paper's "horizontal" SIMD scheme, Sec. 3: partial sums per lane, one horizontal sum
 //     at the end), reading 4 consecutive indices per lane with a 16-byte load;
 //   * the M per-lane partial sums are folded across the wavefront by a halving exchange, the
-//     bias is added once, last, and one lane per row stores the result.
+//     bias is added once, last (then the optional PReLU), and one lane per row stores the result.
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -33,7 +33,7 @@ template <int MM>
 __global__ void __launch_bounds__(kDecodeThreads)
 k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int32_t *__restrict__ csn,
          const int32_t *__restrict__ rip, const int32_t *__restrict__ rin, const float *__restrict__ b,
-         float *__restrict__ Y, int K, int N)
+         const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N)
 {
     extern __shared__ __attribute__((aligned(16))) float xs[];   // [K + 1][MM], row K is all zero
     for (int k = threadIdx.x; k <= K; k += kDecodeThreads) {
@@ -70,7 +70,7 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
         const float bias = b ? b[n] : 0.f;
 #pragma unroll
         for (int m = 0; m < MM; ++m)
-            if (lane == m) Y[(size_t)m * N + n] = acc[m] + bias;
+            if (lane == m) Y[(size_t)m * N + n] = activate(acc[m] + bias, alpha, alpha_stride, n);
     }
 }
 
@@ -89,7 +89,7 @@ int compute_units()
 }
 
 template <int MM>
-hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
 {
     const DeviceTcsc d = device_view(t);
     const size_t lds = (size_t)(t->K + 1) * MM * sizeof(float);
@@ -107,7 +107,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, hipSt
     hipError_t e;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_decode<MM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
-                       d.col_start_neg, d.row_index_pos, d.row_index_neg, b, Y, t->K, t->N);
+                       d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     return e;
@@ -117,17 +117,18 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, hipSt
 
 bool decode_supported(int M, int K) { return M <= 8 && (size_t)(K + 1) * M * sizeof(float) <= (size_t)kDecodeMaxLds; }
 
-hipError_t launch_decode(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                         hipStream_t stream)
 {
     switch (M) {
-    case 1: return launch<1>(X, t, b, Y, stream);
-    case 2: return launch<2>(X, t, b, Y, stream);
-    case 3: return launch<3>(X, t, b, Y, stream);
-    case 4: return launch<4>(X, t, b, Y, stream);
-    case 5: return launch<5>(X, t, b, Y, stream);
-    case 6: return launch<6>(X, t, b, Y, stream);
-    case 7: return launch<7>(X, t, b, Y, stream);
-    case 8: return launch<8>(X, t, b, Y, stream);
+    case 1: return launch<1>(X, t, b, act, Y, stream);
+    case 2: return launch<2>(X, t, b, act, Y, stream);
+    case 3: return launch<3>(X, t, b, act, Y, stream);
+    case 4: return launch<4>(X, t, b, act, Y, stream);
+    case 5: return launch<5>(X, t, b, act, Y, stream);
+    case 6: return launch<6>(X, t, b, act, Y, stream);
+    case 7: return launch<7>(X, t, b, act, Y, stream);
+    case 8: return launch<8>(X, t, b, act, Y, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -23,6 +23,13 @@ inline size_t xt_bytes(int n_kblocks)
 }
 inline size_t workspace_bytes(int n_kblocks) { return kPartialBytes + xt_bytes(n_kblocks); }
 
+// y = v for v > 0, alpha * v otherwise (alpha == nullptr: y = v).  n: column of Y.
+__device__ __forceinline__ float activate(float v, const float *alpha, int alpha_stride, int n)
+{
+    if (alpha == nullptr) return v;
+    return v > 0.f ? v : alpha[(size_t)n * alpha_stride] * v;
+}
+
 }  // namespace tst
 
 struct tcsc {
@@ -61,11 +68,18 @@ inline DeviceTcsc device_view(const tcsc *t)
 // reblock.hip -- GPU pass: TCSC arrays (already on the device) -> per-K-block row sets.
 hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
 // tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 8.
-hipError_t launch_large(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);
+// Optional PReLU behind the bias add: alpha == nullptr means none; alpha_stride 0 = one slope, 1 = one per column.
+struct Activation {
+    const float *alpha;
+    int alpha_stride;
+};
+hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                        hipStream_t stream);
 extern int g_cols_per_wave, g_k_slices, g_slab_tiles;   // tuning overrides, 0 = built-in choice
 extern hipEvent_t g_event_before, g_event_after;       // recorded around the main kernel of a call when set
 // tstgemm_decode.hip -- small-M kernel (M <= 8, whole X resident in the LDS).
 bool decode_supported(int M, int K);
-hipError_t launch_decode(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);
+hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                         hipStream_t stream);
 
 }  // namespace tst

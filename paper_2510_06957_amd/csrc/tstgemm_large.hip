@@ -198,10 +198,12 @@ struct LargeArgs {
     const float *xt;
     const u64 *masks;
     const float *b;
+    const float *alpha;   // PReLU slopes or nullptr
     float *Y;
     float *partials;   // [tile][k_slices][16 NCW columns][TM rows] when k_slices > 1
     int M, N, n_pad, n_kblocks, n_colgroups, k_slices, kb_per_slice;
     int remap;   // workgroups per XCD when the grid is spread evenly over the 8 XCDs, else 0
+    int alpha_stride;
 };
 
 // R rows per lane, NCW columns per wavefront.
@@ -300,7 +302,7 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         return;
     }
 
-    // ---- output: Y = acc + b, bias added once, last
+    // ---- output: Y = acc + b (bias added once, last), then the optional PReLU
     float bias[NCW];
 #pragma unroll
     for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
@@ -314,19 +316,20 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
             if (store_vec) {
                 float4v o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = lane_of<R>(acc[j], r) + bias[j];
+                for (int j = 0; j < 4; ++j)
+                    o[j] = activate(lane_of<R>(acc[j], r) + bias[j], a.alpha, a.alpha_stride, c0 + j);
                 *reinterpret_cast<float4v *>(yrow) = o;
                 continue;
             }
         }
 #pragma unroll
         for (int j = 0; j < NCW; ++j)
-            if (c0 + j < N) yrow[j] = lane_of<R>(acc[j], r) + bias[j];
+            if (c0 + j < N) yrow[j] = activate(lane_of<R>(acc[j], r) + bias[j], a.alpha, a.alpha_stride, c0 + j);
     }
 }
 
 // ------------------------------------------------------------------------------------------------------------------
-// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b.  The partial sums of a workgroup tile are stored
+// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b, then the optional PReLU.  The partial sums of a workgroup tile are stored
 // [column][row]; one workgroup of k_reduce takes kReduceRows rows x C columns of a tile, adds the slices, turns the
 // block round in the LDS and stores rows of Y.  C = 16 NCW columns, TM rows per tile.  The partial sums are read
 // once and were written past the caches, so they are loaded as non-temporal data.
@@ -336,8 +339,8 @@ constexpr int kMaxSlices = 8;
 
 template <int C>
 __global__ void __launch_bounds__(kReduceThreads)
-k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__restrict__ Y, int M, int N, int n_colgroups,
-         int k_slices, int TM)
+k_reduce(const float *__restrict__ P, const float *__restrict__ b, const float *__restrict__ alpha, int alpha_stride,
+         float *__restrict__ Y, int M, int N, int n_colgroups, int k_slices, int TM)
 {
     __shared__ float t[C][kReduceRows + 1];
     constexpr int kRowQuads = kReduceRows / 4;                   // threads along the rows of a column
@@ -385,12 +388,12 @@ k_reduce(const float *__restrict__ P, const float *__restrict__ b, float *__rest
         if (vec) {
             float4v o;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) o[j] = t[4 * q + j][r] + bias[j];
+            for (int j = 0; j < 4; ++j) o[j] = activate(t[4 * q + j][r] + bias[j], alpha, alpha_stride, n + j);
             *reinterpret_cast<float4v *>(dst) = o;
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (n + j < N) dst[j] = t[4 * q + j][r] + bias[j];
+                if (n + j < N) dst[j] = activate(t[4 * q + j][r] + bias[j], alpha, alpha_stride, n + j);
         }
     }
 }
@@ -411,7 +414,8 @@ int compute_units()
 
 // One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles must fit the workspace.
 template <int R, int NCW>
-hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int rows, int k_slices, hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int rows, int k_slices,
+                  hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
@@ -432,6 +436,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
 
     LargeArgs a;
     a.xt = d.xt; a.masks = d.masks; a.b = b; a.Y = Y;
+    a.alpha = act.alpha; a.alpha_stride = act.alpha_stride;
     a.partials = d.partials;
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
@@ -451,14 +456,15 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
     hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / kReduceRows))), dim3(kReduceThreads), 0, stream,
-                       d.partials, b, Y, rows, l.N, a.n_colgroups, k_slices, TM);
+                       d.partials, b, act.alpha, act.alpha_stride, Y, rows, l.N, a.n_colgroups, k_slices, TM);
     return hipGetLastError();
 }
 
 // Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave
 // compute units idle, into as few slices as fill them.  X is processed in slabs of as many row tiles as the
 // workspace holds.
-template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+template <int R>
+hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
@@ -484,9 +490,9 @@ template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, 
         float *Ys = Y + (size_t)m_begin * l.N;
         hipError_t e;
         switch (ncw) {
-        case 1: e = launch<R, 1>(Xs, t, b, Ys, rows, k_slices, stream); break;
-        case 2: e = launch<R, 2>(Xs, t, b, Ys, rows, k_slices, stream); break;
-        default: e = launch<R, 4>(Xs, t, b, Ys, rows, k_slices, stream); break;
+        case 1: e = launch<R, 1>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
+        case 2: e = launch<R, 2>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
+        default: e = launch<R, 4>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
         }
         if (e != hipSuccess) return e;
     }
@@ -495,11 +501,12 @@ template <int R> hipError_t pick(const float *X, const tcsc *t, const float *b, 
 
 }  // namespace
 
-hipError_t launch_large(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                        hipStream_t stream)
 {
-    if (M <= 64) return pick<1>(X, t, b, Y, M, stream);
-    if (M <= 128) return pick<2>(X, t, b, Y, M, stream);
-    return pick<4>(X, t, b, Y, M, stream);
+    if (M <= 64) return pick<1>(X, t, b, act, Y, M, stream);
+    if (M <= 128) return pick<2>(X, t, b, act, Y, M, stream);
+    return pick<4>(X, t, b, act, Y, M, stream);
 }
 
 }  // namespace tst

@@ -192,3 +192,41 @@ def test_profile_events_bracket_the_main_kernel():
     assert 0.0 < ms < 50.0
     Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
     assert_close(Y.cpu().numpy(), Yd, A, "C1 with events")
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 300, 70), (8, 513, 65), (40, 700, 130), (200, 640, 96), (300, 1000, 200)])
+@pytest.mark.parametrize("per_column", [False, True])
+def test_prelu_epilogue(M, K, N, per_column):
+    """The fused PReLU (after the bias add) in the decode kernel, the large-M kernel and the split-K reduction kernel,
+    against the oracle's; integer inputs with power-of-two slopes bit for bit."""
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=61 + M)
+    rng = np.random.default_rng(62)
+    alpha = rng.uniform(-1.5, 2.5, N).astype(np.float32) if per_column else np.array([0.25], np.float32)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Yp, Ap = oracle.prelu(Yd, A, alpha)
+    Y, h = gpu_tstgemm(W, X, b, alpha=alpha)
+    assert (Yd < 0).any() and (Yd > 0).any()
+    assert_close(Y, Yp, Ap, f"prelu {M}x{K}x{N}")
+    # exact: integer X and b, slopes that are powers of two
+    _, Xi, bi = si.make_inputs(M, K, N, 0.5, "int8", seed=63 + M)
+    a2 = (2.0 ** rng.integers(-3, 3, N)).astype(np.float32) * rng.choice([-1.0, 1.0], N).astype(np.float32) \
+        if per_column else np.array([0.5], np.float32)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
+    Ypi, _ = oracle.prelu(Ydi, None, a2)
+    Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h, alpha=a2)
+    assert_exact(Yi, Ypi, f"prelu integer {M}x{K}x{N}")
+
+
+def test_prelu_rejects_bad_slopes():
+    import torch
+    W, X, b = si.make_inputs(4, 64, 8, 0.5, "normal", seed=64)
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    with pytest.raises(ValueError):
+        tg.tstgemm(torch.from_numpy(X).cuda(), t, alpha=torch.zeros(3, device="cuda"))
+    lib = tg.binding._load()
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.empty((4, 8), device="cuda")
+    assert lib.tstgemm_prelu(Xd.data_ptr(), t.handle, None, None, 1, Yd.data_ptr(), 4, 64, 8, None) == -1
+    a = torch.zeros(8, device="cuda")
+    assert lib.tstgemm_prelu(Xd.data_ptr(), t.handle, None, a.data_ptr(), 3, Yd.data_ptr(), 4, 64, 8, None) == -1

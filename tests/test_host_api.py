@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(str(tg.library_path()))
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tstgemm_profile_events", "tcsc_destroy",
+            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_set_tuning", "tstgemm_profile_events",
+            "tcsc_destroy",
             "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
