@@ -110,8 +110,8 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * the -1 rows, bias added once at the end).
  * X: DEVICE fp32 M*K row-major.  b: DEVICE fp32 N, or NULL for b = 0.  Y: DEVICE fp32 M*N
  * row-major, fully overwritten; must not overlap X, b or the handle's device buffer.
- * M >= 1 arbitrary; K, N must equal the handle's.  M <= 8 with (K + 1) * M * 4 <= 150 KiB takes the small-M
- * kernel (all of X resident in the LDS, TCSC lists streamed), everything else the large-M path.  Asynchronous: the kernels are enqueued on
+ * M >= 1 arbitrary; K, N must equal the handle's.  M <= 8 takes the small-M kernel (X resident in the LDS, in
+ * chunks of K if it is larger than 150 KiB; TCSC lists streamed), everything else the large-M path.  Asynchronous: the kernels are enqueued on
  * `stream` (a hipStream_t, NULL = null stream), no host synchronisation, no allocation.
  * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, EHIP (launch failure).
  * Rounding: fp32 accumulation in an order fixed by (M, K, N), the matrix and the tuning

@@ -3,8 +3,11 @@
 // With so few rows the operation moves more index bytes than it does additions (the paper's
 // operational-intensity argument, Sec. 4), so the kernel is shaped around streaming the TCSC
 // index arrays (Sec. 2) from HBM exactly once, fully coalesced, in their original form:
-//   * all of X (M x K fp32) is kept in the LDS, transposed to xs[k][m], so one gathered index
-//     yields the M operands of all rows at once;
+//   * X (M x K fp32) is kept in the LDS, transposed to xs[k][m], so one gathered index yields
+//     the M operands of all rows at once.  If all of X does not fit, K is cut into chunks of
+//     as many rows as fit (the paper's K-blocking, Sec. 3, with the LDS in the place of the L1
+//     cache) and the chunks are taken one after the other; the lists are ascending, so the
+//     part of a list that falls into a chunk is contiguous and a cursor per list is enough;
 //   * one wavefront per column; its 64 lanes split the column's +1 list and then its -1 list
 //     (the paper's "horizontal" SIMD scheme, Sec. 3: partial sums per lane, one horizontal sum
 //     at the end), reading 4 consecutive indices per lane with a 16-byte load;
@@ -16,6 +19,7 @@ namespace tst {
 namespace {
 
 constexpr int kDecodeThreads = 1024;
+constexpr int kDecodeWaves = kDecodeThreads / 64;
 constexpr int kDecodeMaxLds = 150 * 1024;
 typedef int int4v __attribute__((ext_vector_type(4)));
 
@@ -29,43 +33,93 @@ template <int MM> __device__ __forceinline__ void wave_sum(float (&v)[MM])
     }
 }
 
-template <int MM>
+// Rows of X a chunk holds for MM rows of X: all of the LDS budget but one row of zeros.
+template <int MM> constexpr int chunk_rows() { return kDecodeMaxLds / (MM * (int)sizeof(float)) - 1; }
+
+// The part of the ascending list rows[p .. p1) with row numbers below k_hi: gathered and added to (SIGN: subtracted
+// from) acc; p moves to the first entry that was not consumed.  xs_base points k_lo rows in front of the chunk in
+// the LDS, so that xs_base[k * MM + m] is X[m][k] for k in [k_lo, k_hi); row k_zero of that view holds zeros.
+// The sweep is 16-byte aligned, in rounds of 256 entries per wavefront; slots in front of p or behind the last
+// consumed entry gather the row of zeros.  CHUNKED = false: the chunk is all of K, nothing can be late.
+template <int MM, bool SIGN, bool CHUNKED>
+__device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__restrict__ rows, int &p, int p1, int k_hi,
+                                            int k_zero, const float *xs_base, int lane)
+{
+    while (p < p1) {
+        const int i = (p & ~3) + lane * 4;
+        int4v q = {0, 0, 0, 0};
+        if (i < p1) q = *reinterpret_cast<const int4v *>(rows + i);
+        int first_late = 4;   // first slot of this lane that belongs to a later chunk
+#pragma unroll
+        for (int e = 3; e >= 0; --e) {
+            const bool live = i + e >= p && i + e < p1;
+            const bool late = CHUNKED && live && q[e] >= k_hi;
+            if (late) first_late = e;
+            const int k = (live && !late) ? q[e] : k_zero;
+#pragma unroll
+            for (int m = 0; m < MM; ++m) {
+                if (SIGN) acc[m] -= xs_base[(size_t)k * MM + m]; else acc[m] += xs_base[(size_t)k * MM + m];
+            }
+        }
+        const unsigned long long late_lanes = CHUNKED ? __ballot(first_late < 4) : 0ull;
+        if (late_lanes == 0) {
+            p = (p & ~3) + 256;   // the whole round was consumed (or lay behind p1)
+        } else {
+            const int l = __builtin_ctzll(late_lanes);
+            p = (p & ~3) + 4 * l + __builtin_amdgcn_readlane(first_late, l);
+            return;               // the rest of the list belongs to later chunks
+        }
+    }
+    p = p1;
+}
+
+template <int MM, bool CHUNKED>
 __global__ void __launch_bounds__(kDecodeThreads)
 k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int32_t *__restrict__ csn,
          const int32_t *__restrict__ rip, const int32_t *__restrict__ rin, const float *__restrict__ b,
-         const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N)
+         const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N, int kc)
 {
-    extern __shared__ __attribute__((aligned(16))) float xs[];   // [K + 1][MM], row K is all zero
-    for (int k = threadIdx.x; k <= K; k += kDecodeThreads) {
-#pragma unroll
-        for (int m = 0; m < MM; ++m) xs[k * MM + m] = k < K ? X[(size_t)m * K + k] : 0.f;
-    }
-    __syncthreads();
-
+    extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc + 1][MM], row kc is all zero
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int waves_total = gridDim.x * (kDecodeThreads / 64);
-    for (int n = blockIdx.x * (kDecodeThreads / 64) + wave; n < N; n += waves_total) {
+    const int waves_total = gridDim.x * kDecodeWaves;
+    const int n_chunks = CHUNKED ? (K + kc - 1) / kc : 1;
+    const int n_batches = (N + waves_total - 1) / waves_total;
+
+    auto load_chunk = [&](int c) {
+        const int k_lo = c * kc, len = min(kc, K - k_lo);
+        for (int k = threadIdx.x; k < len; k += kDecodeThreads) {
+#pragma unroll
+            for (int m = 0; m < MM; ++m) xs[k * MM + m] = X[(size_t)m * K + k_lo + k];
+        }
+    };
+    if (threadIdx.x < MM) xs[kc * MM + threadIdx.x] = 0.f;
+    if (!CHUNKED) load_chunk(0);   // all of X fits: loaded once, for all columns of this workgroup
+    __syncthreads();
+
+    // Every wavefront of the workgroup goes through the same number of batches and chunks (the barriers inside);
+    // a wavefront without a column in the last batch just has empty lists.
+    for (int batch = 0; batch < n_batches; ++batch) {
+        const int n = batch * waves_total + blockIdx.x * kDecodeWaves + wave;
+        const bool have = n < N;
+        int pp = have ? csp[n] : 0, pp1 = have ? csp[n + 1] : 0;
+        int pn = have ? csn[n] : 0, pn1 = have ? csn[n + 1] : 0;
         float acc[MM];
 #pragma unroll
         for (int m = 0; m < MM; ++m) acc[m] = 0.f;
-#pragma unroll
-        for (int sign = 0; sign < 2; ++sign) {
-            const int32_t *__restrict__ rows = sign ? rin : rip;
-            const int p0 = sign ? csn[n] : csp[n], p1 = sign ? csn[n + 1] : csp[n + 1];
-            // 16-byte aligned sweep over [p0, p1): slots outside the range gather the zero row K
-            for (int i = (p0 & ~3) + lane * 4; i < p1; i += 256) {
-                const int4v q = *reinterpret_cast<const int4v *>(rows + i);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int k = (i + e >= p0 && i + e < p1) ? q[e] : K;
-#pragma unroll
-                    for (int m = 0; m < MM; ++m) {
-                        if (sign) acc[m] -= xs[k * MM + m]; else acc[m] += xs[k * MM + m];
-                    }
-                }
+        for (int c = 0; c < n_chunks; ++c) {
+            if (CHUNKED) {
+                __syncthreads();   // everybody is done with the previous chunk
+                load_chunk(c);
+                __syncthreads();
             }
+            const int k_lo = c * kc;
+            const int k_hi = (c + 1 == n_chunks) ? 0x7fffffff : k_lo + kc;
+            const float *xs_base = xs - (size_t)k_lo * MM;
+            run_sublist<MM, false, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
+            run_sublist<MM, true, CHUNKED>(acc, rin, pn, pn1, k_hi, k_lo + kc, xs_base, lane);
         }
+        if (!have) continue;
         wave_sum<MM>(acc);
         const float bias = b ? b[n] : 0.f;
 #pragma unroll
@@ -92,22 +146,31 @@ template <int MM>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
 {
     const DeviceTcsc d = device_view(t);
-    const size_t lds = (size_t)(t->K + 1) * MM * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
+    const int kc = t->K < chunk_rows<MM>() ? t->K : chunk_rows<MM>();
+    const size_t lds = (size_t)(kc + 1) * MM * sizeof(float);
+    const bool chunked = t->K > kc;
+    const void *kernel = chunked ? reinterpret_cast<const void *>(&k_decode<MM, true>)
+                                 : reinterpret_cast<const void *>(&k_decode<MM, false>);
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[chunked]) {
+        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[chunked] = true;
     }
     const int per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
     int grid = compute_units() * per_cu;
-    const int need = (t->N + kDecodeThreads / 64 - 1) / (kDecodeThreads / 64);
+    const int need = (t->N + kDecodeWaves - 1) / kDecodeWaves;
     if (grid > need) grid = need;
     hipError_t e;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_decode<MM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
-                       d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N);
+    if (chunked)
+        hipLaunchKernelGGL((k_decode<MM, true>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
+                           d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K,
+                           t->N, kc);
+    else
+        hipLaunchKernelGGL((k_decode<MM, false>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
+                           d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K,
+                           t->N, kc);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     return e;
@@ -115,7 +178,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
 
 }  // namespace
 
-bool decode_supported(int M, int K) { return M <= 8 && (size_t)(K + 1) * M * sizeof(float) <= (size_t)kDecodeMaxLds; }
+bool decode_supported(int M, int K) { (void)K; return M <= 8; }
 
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream)

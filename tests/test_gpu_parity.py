@@ -230,3 +230,20 @@ def test_prelu_rejects_bad_slopes():
     assert lib.tstgemm_prelu(Xd.data_ptr(), t.handle, None, None, 1, Yd.data_ptr(), 4, 64, 8, None) == -1
     a = torch.zeros(8, device="cuda")
     assert lib.tstgemm_prelu(Xd.data_ptr(), t.handle, None, a.data_ptr(), 3, Yd.data_ptr(), 4, 64, 8, None) == -1
+
+
+@pytest.mark.parametrize("M,K,N", [(8, 4799, 40), (8, 4800, 40), (8, 8229, 70), (5, 20000, 33), (1, 40001, 20),
+                                   (2, 77000, 9)])
+def test_decode_k_chunks(M, K, N):
+    """M <= 8 with more of X than the LDS holds: K is taken in chunks, each list is consumed chunk by chunk (at the
+    chunk border a round of 256 indices is split between two chunks); real inputs within tolerance, integer inputs
+    bit for bit."""
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=71 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"decode chunks {M}x{K}x{N}")
+    _, Xi, bi = si.make_inputs(M, K, N, 0.5, "int8", seed=72 + M)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
+    Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h)
+    assert_exact(Yi, Ydi, f"decode chunks integer {M}x{K}x{N}")
