@@ -81,16 +81,22 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *
  *   masks      uint64 [n_kblocks][n_pad][2]   [kb][n][0]: the +1 rows of column n inside K-block
  *                                             kb, [kb][n][1]: the -1 rows
+ *   list_cuts  int32  [n_cuts + 1][n_pad][2]  for the small-tile kernel (M <= 64): the lists cut at multiples of
+ *                                             cut_rows = 256 rows, as positions inside row_index_pos / _neg.
+ *                                             [c][n][0]: index of the first entry of column n's +1 list whose row
+ *                                             is >= c * 256 (c = n_cuts: the end of the list), [c][n][1]: the same
+ *                                             for the -1 list.  Rows ascend inside a list, so the piece of a list
+ *                                             inside a block of 256 rows is the slice between two cuts.
  *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): split-K partial sums (32 MiB) and a tiled,
  *                                             transposed copy of (a slab of rows of) X (128 MiB, or one tile of
  *                                             256 rows over the padded K if that is larger)
  * n_pad = N rounded up to a multiple of 64; columns >= N have empty sets.
  */
 typedef struct tcsc_layout {
-    int32_t K, N, n_pad, k_block, n_kblocks, reserved;
+    int32_t K, N, n_pad, k_block, n_kblocks, n_cuts;   /* n_cuts = K / 256 rounded up */
     int64_t nnz_pos, nnz_neg;
     size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
-    size_t off_masks, off_workspace, workspace_bytes, total_bytes;
+    size_t off_masks, off_list_cuts, off_workspace, workspace_bytes, total_bytes;
 } tcsc_layout_t;
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);

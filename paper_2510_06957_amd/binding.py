@@ -23,11 +23,11 @@ class TstgemmError(RuntimeError):
 
 class TcscLayout(ctypes.Structure):
     _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("n_pad", ctypes.c_int32), ("k_block", ctypes.c_int32),
-                ("n_kblocks", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("n_kblocks", ctypes.c_int32), ("n_cuts", ctypes.c_int32),
                 ("nnz_pos", ctypes.c_int64), ("nnz_neg", ctypes.c_int64),
                 ("off_col_start_pos", ctypes.c_size_t), ("off_col_start_neg", ctypes.c_size_t),
                 ("off_row_index_pos", ctypes.c_size_t), ("off_row_index_neg", ctypes.c_size_t),
-                ("off_masks", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
+                ("off_masks", ctypes.c_size_t), ("off_list_cuts", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
                 ("workspace_bytes", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
 
 

@@ -17,7 +17,8 @@ HERE = pathlib.Path(__file__).resolve().parent
 ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libtstgemm.so"
-SOURCES = ["tcsc_host.cpp", "reblock.hip", "tstgemm_large.hip", "tstgemm_decode.hip"]
+SOURCES = ["tcsc_host.cpp", "reblock.hip", "tstgemm_side.hip", "tstgemm_large.hip", "tstgemm_small.hip",
+           "tstgemm_decode.hip"]
 ARCH = "gfx950"
 
 

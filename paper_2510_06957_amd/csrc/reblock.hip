@@ -8,7 +8,10 @@
 // kept as a 64-bit set of block-local row numbers instead of a list of 32-bit indices
 // (layout: tcsc_layout_t in tstgemm.h).
 //
-// Integer work only; one small kernel, run once per matrix at upload time.
+// A second small kernel cuts the lists at multiples of 256 rows for the small-tile kernel, which walks the
+// original lists: it only needs to know where each block's slice starts.
+//
+// Integer work only, run once per matrix at upload time.
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -52,6 +55,24 @@ k_row_sets(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, con
     masks[2 * id + 1] = neg;
 }
 
+// One thread per (cut, column): where the rows >= cut * kCutRows start in the column's two lists.
+__global__ void __launch_bounds__(kThreads)
+k_list_cuts(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, const int32_t *__restrict__ rip,
+            const int32_t *__restrict__ rin, int32_t *__restrict__ cuts, int N, int n_pad, int n_cuts)
+{
+    const long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (id >= (long long)n_pad * (n_cuts + 1)) return;
+    const int n = (int)(id % n_pad), c = (int)(id / n_pad);
+    int pos = 0, neg = 0;
+    if (n < N) {
+        const long long row = (long long)c * kCutRows;
+        pos = c == n_cuts ? csp[n + 1] : lower_bound_dev(rip, csp[n], csp[n + 1], (int)row);
+        neg = c == n_cuts ? csn[n + 1] : lower_bound_dev(rin, csn[n], csn[n + 1], (int)row);
+    }
+    cuts[2 * id] = pos;
+    cuts[2 * id + 1] = neg;
+}
+
 }  // namespace
 
 hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
@@ -62,6 +83,12 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
     const unsigned grid = (unsigned)((cells + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(k_row_sets, dim3(grid), dim3(kThreads), 0, stream, d.col_start_pos, d.col_start_neg,
                        d.row_index_pos, d.row_index_neg, d.masks, l.N, l.n_pad, l.n_kblocks);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long cut_cells = (long long)l.n_pad * (l.n_cuts + 1);
+    hipLaunchKernelGGL(k_list_cuts, dim3((unsigned)((cut_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                       d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.list_cuts, l.N, l.n_pad,
+                       l.n_cuts);
     return hipGetLastError();
 }
 

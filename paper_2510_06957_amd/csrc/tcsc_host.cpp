@@ -19,17 +19,18 @@ void compute_layout(tcsc *t)
     l.n_pad = (t->N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
     l.k_block = tst::kKBlock;
     l.n_kblocks = (t->K + tst::kKBlock - 1) / tst::kKBlock;
-    l.reserved = 0;
+    l.n_cuts = (t->K + tst::kCutRows - 1) / tst::kCutRows;
     l.nnz_pos = (int64_t)t->row_index_pos.size();
     l.nnz_neg = (int64_t)t->row_index_neg.size();
     size_t off = 0;
     auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     l.off_col_start_pos = place(sizeof(int32_t) * (size_t)(t->N + 1));
     l.off_col_start_neg = place(sizeof(int32_t) * (size_t)(t->N + 1));
-    // + 4 entries of slack: the small-M kernel reads the lists in aligned groups of four
-    l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + 4));
-    l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + 4));
+    // + slack: the kernels read the lists in groups of four and sixteen entries
+    l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + tst::kIndexSlack));
+    l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + tst::kIndexSlack));
     l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
+    l.off_list_cuts = place(2 * sizeof(int32_t) * (size_t)(l.n_cuts + 1) * (size_t)l.n_pad);
     l.workspace_bytes = tst::workspace_bytes(l.n_kblocks);
     l.off_workspace = place(l.workspace_bytes);
     l.total_bytes = off;
@@ -218,6 +219,7 @@ int run(const float *X, const tcsc_t *t, const float *b, const tst::Activation &
     if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, act, Y, M, s)
+                   : M <= 64                   ? tst::launch_small(X, t, b, act, Y, M, s)
                                                : tst::launch_large(X, t, b, act, Y, M, s);
     return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
 }

@@ -128,20 +128,6 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
     }
 }
 
-int compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
-
 template <int MM>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
 {

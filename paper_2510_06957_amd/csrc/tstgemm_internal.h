@@ -12,6 +12,8 @@ namespace tst {
 // Geometry of the K-blocked device form (see tcsc_layout_t in tstgemm.h).
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
+constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
+constexpr int kIndexSlack = 16;   // entries behind each index array that may be read (never used)
 constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: [k_slices][padded rows][n_pad] fp32
 constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
 
@@ -46,6 +48,7 @@ namespace tst {
 struct DeviceTcsc {
     const int32_t *col_start_pos, *col_start_neg, *row_index_pos, *row_index_neg;
     unsigned long long *masks;   // [n_kblocks][n_pad][2]
+    int32_t *list_cuts;          // [n_cuts + 1][n_pad][2]
     float *partials;     // split-K partial sums
     float *xt;           // xt[tile][k][row]: row tiles of (a slab of) X, transposed, zero padded
     size_t xt_capacity;  // bytes
@@ -60,19 +63,31 @@ inline DeviceTcsc device_view(const tcsc *t)
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_pos),
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_neg),
                       reinterpret_cast<unsigned long long *>(d + l.off_masks),
+                      reinterpret_cast<int32_t *>(d + l.off_list_cuts),
                       reinterpret_cast<float *>(d + l.off_workspace),
                       reinterpret_cast<float *>(d + l.off_workspace + kPartialBytes),
                       xt_bytes(l.n_kblocks)};
 }
 
-// reblock.hip -- GPU pass: TCSC arrays (already on the device) -> per-K-block row sets.
-hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
-// tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 8.
 // Optional PReLU behind the bias add: alpha == nullptr means none; alpha_stride 0 = one slope, 1 = one per column.
 struct Activation {
     const float *alpha;
     int alpha_stride;
 };
+// reblock.hip -- GPU pass: TCSC arrays (already on the device) -> per-K-block row sets.
+hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
+// tstgemm_side.hip -- X packing pre-pass and split-K reduction, shared by the tiled paths.
+constexpr int kMaxKSlices = 8;
+int compute_units();
+// X (rows x K, row-major) -> xt[tile][k_pad][TM] (TM = 64, 128 or 256 rows per tile, k_pad a multiple of 64), zero padded.
+hipError_t launch_pack(const float *X, float *xt, int rows, int K, int k_pad, int TM, hipStream_t stream);
+// Y = sum of the k_slices partial tiles ([tile][slice][C columns][TM rows], C = 16, 32 or 64) in slice order + b, then act.
+hipError_t launch_reduce(int C, const float *partials, const float *b, const Activation &act, float *Y, int M, int N,
+                         int m_tiles, int n_colgroups, int k_slices, int TM, hipStream_t stream);
+// tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (64-row tiles).
+hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                        hipStream_t stream);
+// tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 64.
 hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream);
 extern int g_cols_per_wave, g_k_slices, g_slab_tiles;   // tuning overrides, 0 = built-in choice

@@ -146,54 +146,6 @@ __device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set,
 }
 
 // ------------------------------------------------------------------------------------------------------------------
-// k_pack_x: X (rows m_begin .. m_begin + rows) -> xt[tile][k_pad][TM], zero padded.  One workgroup per (K-block,
-// 64 rows): 64 x 64 floats go through the LDS so that both the reads (along k) and the writes (along rows) are
-// contiguous.  VEC: rows of X are 16-byte aligned and K is a multiple of 4.
-constexpr int kPackThreads = 256;
-
-template <bool VEC>
-__global__ void __launch_bounds__(kPackThreads)
-k_pack_x(const float *__restrict__ X, float *__restrict__ xt, int rows, int K, int k_pad, int TM)
-{
-    __shared__ float t[64][65];
-    const int kb = blockIdx.x, m0 = blockIdx.y * 64;
-    const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
-    const int k = kb * 64 + 4 * c;
-    // The four loads are issued unconditionally, so that they are all in flight together: rows beyond the last one
-    // read the last row, pieces beyond K read the start of the row, and both are zeroed afterwards.
-    float4v v[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int m = m0 + r + 16 * p;
-        const float *src = X + (size_t)min(m, rows - 1) * K;
-        if constexpr (VEC) {
-            v[p] = *reinterpret_cast<const float4v *>(src + (k < K ? k : 0));   // K % 4 == 0: inside or outside as a whole
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[p][j] = src[k + j < K ? k + j : 0];
-        }
-    }
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int row = r + 16 * p;
-        const bool row_ok = m0 + row < rows;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) t[4 * c + j][row] = (row_ok && k + j < K) ? v[p][j] : 0.f;
-    }
-    __syncthreads();
-    const int kk = threadIdx.x >> 2, q = threadIdx.x & 3;
-    const int tile = m0 / TM, r0 = m0 % TM;
-    float *dst = xt + ((size_t)tile * k_pad + (size_t)kb * 64 + kk) * TM + r0 + 16 * q;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float4v o;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = t[kk][16 * q + 4 * i + j];
-        *reinterpret_cast<float4v *>(dst + 4 * i) = o;
-    }
-}
-
-// ------------------------------------------------------------------------------------------------------------------
 struct LargeArgs {
     const float *xt;
     const u64 *masks;
@@ -328,90 +280,6 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     }
 }
 
-// ------------------------------------------------------------------------------------------------------------------
-// k_reduce: Y = (slice 0 + slice 1 + ... in this order) + b, then the optional PReLU.  The partial sums of a workgroup tile are stored
-// [column][row]; one workgroup of k_reduce takes kReduceRows rows x C columns of a tile, adds the slices, turns the
-// block round in the LDS and stores rows of Y.  C = 16 NCW columns, TM rows per tile.  The partial sums are read
-// once and were written past the caches, so they are loaded as non-temporal data.
-constexpr int kReduceThreads = 256;
-constexpr int kReduceRows = 32;
-constexpr int kMaxSlices = 8;
-
-template <int C>
-__global__ void __launch_bounds__(kReduceThreads)
-k_reduce(const float *__restrict__ P, const float *__restrict__ b, const float *__restrict__ alpha, int alpha_stride,
-         float *__restrict__ Y, int M, int N, int n_colgroups, int k_slices, int TM)
-{
-    __shared__ float t[C][kReduceRows + 1];
-    constexpr int kRowQuads = kReduceRows / 4;                   // threads along the rows of a column
-    constexpr int kColsPerPass = kReduceThreads / kRowQuads;
-    static_assert(C % kColsPerPass == 0 || kColsPerPass % C == 0, "column passes");
-    const int sub_per_tile = TM / kReduceRows;
-    const int group = blockIdx.x / sub_per_tile, sub = blockIdx.x % sub_per_tile;
-    const int mt = group / n_colgroups, cg = group % n_colgroups;
-    const size_t tile_floats = (size_t)C * TM;
-    const float *base = P + (size_t)group * k_slices * tile_floats + (size_t)sub * kReduceRows;
-    const int rr = (threadIdx.x % kRowQuads) * 4;
-#pragma unroll
-    for (int pass = 0; pass < (C + kColsPerPass - 1) / kColsPerPass; ++pass) {
-        const int c = pass * kColsPerPass + threadIdx.x / kRowQuads;
-        if (C < kColsPerPass && c >= C) break;
-        const float *src = base + (size_t)c * TM + rr;
-        // all slices are requested before the first addition; the additions then run in slice order
-        float4v part[kMaxSlices];
-#pragma unroll
-        for (int s = 0; s < kMaxSlices; ++s)
-            part[s] = __builtin_nontemporal_load(
-                reinterpret_cast<const float4v *>(src + (size_t)(s < k_slices ? s : 0) * tile_floats));
-        float4v sum = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < kMaxSlices; ++s)
-            if (s < k_slices) sum += part[s];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) t[c][rr + i] = sum[i];
-    }
-    __syncthreads();
-    constexpr int kQuads = C / 4;                          // float4 pieces of an output row
-    constexpr int kRowsPerPass = kReduceThreads / kQuads;
-    const int q = threadIdx.x % kQuads;
-    const int n = cg * C + 4 * q;
-    const bool vec = (N % 4 == 0) && (n + 4 <= N) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
-    float bias[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) bias[j] = (b != nullptr && n + j < N) ? b[n + j] : 0.f;
-#pragma unroll
-    for (int pass = 0; pass < (kReduceRows + kRowsPerPass - 1) / kRowsPerPass; ++pass) {
-        const int r = pass * kRowsPerPass + threadIdx.x / kQuads;
-        const int m = mt * TM + sub * kReduceRows + r;
-        if (r >= kReduceRows || m >= M) continue;
-        float *dst = Y + (size_t)m * N + n;
-        if (vec) {
-            float4v o;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) o[j] = activate(t[4 * q + j][r] + bias[j], alpha, alpha_stride, n + j);
-            *reinterpret_cast<float4v *>(dst) = o;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (n + j < N) dst[j] = activate(t[4 * q + j][r] + bias[j], alpha, alpha_stride, n + j);
-        }
-    }
-}
-
-int compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
-
 // One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles must fit the workspace.
 template <int R, int NCW>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int rows, int k_slices,
@@ -424,14 +292,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     const long long m_tiles = (rows + TM - 1) / TM;
     if ((size_t)m_tiles * k_pad * TM * sizeof(float) > d.xt_capacity) return hipErrorInvalidValue;
 
-    const bool vec = (l.K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    const dim3 pgrid((unsigned)l.n_kblocks, (unsigned)(m_tiles * (TM / 64)));
-    if (pgrid.y > 65535u) return hipErrorInvalidValue;
-    if (vec)
-        hipLaunchKernelGGL((k_pack_x<true>), pgrid, dim3(kPackThreads), 0, stream, X, d.xt, rows, l.K, k_pad, TM);
-    else
-        hipLaunchKernelGGL((k_pack_x<false>), pgrid, dim3(kPackThreads), 0, stream, X, d.xt, rows, l.K, k_pad, TM);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_pack(X, d.xt, rows, l.K, k_pad, TM, stream);
     if (e != hipSuccess) return e;
 
     LargeArgs a;
@@ -441,23 +302,21 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
     const long long groups = m_tiles * a.n_colgroups;
-    if (k_slices > kMaxSlices) k_slices = kMaxSlices;
+    if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
     const size_t slice_bytes = (size_t)groups * NW * NCW * TM * sizeof(float);
     if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
     const long long grid = groups * k_slices;
-    if (grid > 0x7fffffffLL || groups * (TM / kReduceRows) > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
-    hipLaunchKernelGGL((k_reduce<NW * NCW>), dim3((unsigned)(groups * (TM / kReduceRows))), dim3(kReduceThreads), 0, stream,
-                       d.partials, b, act.alpha, act.alpha_stride, Y, rows, l.N, a.n_colgroups, k_slices, TM);
-    return hipGetLastError();
+    return launch_reduce(NW * NCW, d.partials, b, act, Y, rows, l.N, (int)m_tiles, a.n_colgroups, k_slices, TM, stream);
 }
 
 // Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave

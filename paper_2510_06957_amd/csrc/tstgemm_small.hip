@@ -1,0 +1,259 @@
+// Small-tile kernel of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper) for 8 < M <= 64.
+//
+// Arithmetic is that of BaseTCSC (Sec. 2): gather-add the +1 list, gather-subtract the -1 list, bias added once at
+// the end; no multiplications.  With at most 64 rows of X a wavefront has more lanes than rows, so the mapping
+// differs from the large-M kernel's:
+//
+//   * the 64 lanes form 4 groups of 16; a lane owns 4 consecutive rows of X, a group all 64 rows of the tile;
+//   * the four groups take four consecutive members of the SAME list at a time (the paper's "horizontal" scheme,
+//     Sec. 3, between the groups; its "vertical" scheme inside a group): one ds_read_b128 of the wavefront gathers
+//     four tile rows, one per group, and every group keeps its own partial sums, which are added across the groups
+//     once, at the end of the K slice (a fixed order);
+//   * the members come straight from the TCSC arrays (Sec. 2): the lists are ascending, so the piece of a list that
+//     falls into a block of 256 rows of W (the paper's blocking, Sec. 3) is a slice of row_index_pos / _neg; the
+//     re-blocking pass stores where the slices start (list_cuts).  A lane loads 4 consecutive row numbers with one
+//     16-byte load, 16 per wavefront, one load ahead of their use; a row number costs one VALU instruction (shift
+//     and add to the lane's LDS address) and no scalar work;
+//   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of 256 rows of the packed X tile in the LDS
+//     (64 KiB, tile[k][64 rows]) with a row of zeros in front of it for the slots behind the end of a slice; two
+//     workgroups share a compute unit, one computes while the other exchanges its tile;
+//   * split K, packing pre-pass and reduction as in the large-M path.
+#include "tstgemm_internal.h"
+
+namespace tst {
+namespace {
+
+constexpr int NW = 16;        // wavefronts per workgroup
+constexpr int NT = NW * 64;   // threads per workgroup
+constexpr int TM = 64;        // rows of X per tile
+constexpr int RB = TM * 4;    // bytes of a tile row
+constexpr int STAGE = kCutRows * RB;          // bytes of one block of the tile (64 KiB)
+constexpr int LPT = STAGE / (NT * 16);        // 16-byte pieces per thread and block
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int4v int4v_unaligned __attribute__((aligned(4)));   // the lists start at any entry: 4-byte aligned 16-byte loads
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;   // read through the scalar cache
+
+struct SmallArgs {
+    const float *xt;            // xt[k_pad][64]: the one tile of X, packed
+    const int32_t *cuts;        // [n_cuts + 1][n_pad][2]
+    const int32_t *rip, *rin;   // row_index_pos / row_index_neg
+    const float *b;
+    const float *alpha;
+    float *Y;
+    float *partials;            // [colgroup][k_slices][16 NCW columns][64 rows] when k_slices > 1
+    int M, N, n_pad, n_cuts, n_colgroups, k_slices, cuts_per_slice;
+    int remap, alpha_stride;
+};
+
+// Four gathers of the wavefront: tile rows k[0..3] (per lane group), this lane's four X rows of each.  base is the
+// lane's LDS address of row 0 of the W block minus the block's first row times the row size, so that
+// address = (row number << 8) + base needs no subtraction.
+typedef const __attribute__((address_space(3))) float4v *lds_f4_ptr;
+__device__ __forceinline__ void gather4(float4v (&v)[4], const int4v &k, int base)
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) v[t] = *reinterpret_cast<lds_f4_ptr>((k[t] << 8) + base);
+}
+
+// The slice rows[lo .. hi) of a list: lane group g takes entries 16 c + 4 g .. + 3 of chunk c; q holds the lane's
+// entries of chunk 0 (loaded by the caller, one slice ahead).  Entries behind hi (up to 15 are loaded beyond the end
+// of a slice; the index arrays have that much slack) are replaced by k_zero, the row in front of the block, which
+// holds zeros.
+template <bool NEG>
+__device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *__restrict__ p, int n, int base,
+                                          int k_zero, int g)
+{
+    // p = rows + lo + 4 g
+    for (int c = 16; c <= n; c += 16) {
+        const int4v cur = q;
+        q = *reinterpret_cast<const int4v_unaligned *>(p + c);
+        float4v v[4];
+        gather4(v, cur, base);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if constexpr (NEG) acc -= v[t]; else acc += v[t];
+        }
+    }
+    const int rem = n & 15;
+    if (n > 0 && rem) {
+        int4v cur;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) cur[t] = (4 * g + t < rem) ? q[t] : k_zero;
+        float4v v[4];
+        gather4(v, cur, base);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if constexpr (NEG) acc -= v[t]; else acc += v[t];
+        }
+    }
+}
+
+template <int NCW>
+__global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then tile rows 0 .. 255
+    char *const tile = lds + RB;
+    const int M = a.M, N = a.N;
+    const int lane = threadIdx.x & 63, g = lane >> 4, r = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    int wg = blockIdx.x;
+    if (a.remap) wg = (wg & 7) * a.remap + (wg >> 3);
+    const int cg = wg % a.n_colgroups, slice = wg / a.n_colgroups;
+    const int c0 = (cg * NW + wave) * NCW;   // < n_pad by construction of the grid
+    const int cut0 = min(slice * a.cuts_per_slice, a.n_cuts);
+    const int cut1 = min(cut0 + a.cuts_per_slice, a.n_cuts);
+
+    float4v acc[NCW];
+#pragma unroll
+    for (int j = 0; j < NCW; ++j) acc[j] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    if (cut0 < cut1) {
+        const char *xtile = reinterpret_cast<const char *>(a.xt);
+        const int piece = threadIdx.x * 16;
+        float4v st[LPT];
+        auto stage_load = [&](int c) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i)
+                st[i] = *reinterpret_cast<const float4v *>(xtile + (size_t)c * STAGE + (piece + i * NT * 16));
+        };
+        auto stage_store = [&]() {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) *reinterpret_cast<float4v *>(tile + piece + i * NT * 16) = st[i];
+        };
+        // slice borders of (cut, c0 .. c0+NCW-1): 2 NCW consecutive ints per cut (column j: +1 list, -1 list)
+        const const_i32_ptr cuts_base =
+            reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(a.cuts)) + (size_t)c0 * 2;
+        const size_t cuts_stride = (size_t)a.n_pad * 2;
+        int lo[2 * NCW], hi[2 * NCW];
+        auto load_cut = [&](int (&dst)[2 * NCW], int c) {
+#pragma unroll
+            for (int i = 0; i < 2 * NCW; ++i) dst[i] = cuts_base[(size_t)c * cuts_stride + i];
+        };
+
+        if (threadIdx.x < RB / 4) reinterpret_cast<float *>(lds)[threadIdx.x] = 0.f;
+        load_cut(lo, cut0);
+        stage_load(cut0);
+        stage_store();
+        __syncthreads();
+        const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+        const int lane_base = lds0 + RB + r * 16;     // this lane's part of tile row 0
+        // first chunk of a slice: this lane's 4 entries, loaded one slice ahead of their use
+        auto first_chunk = [&](const int32_t *rows, int at) { return int4v(*reinterpret_cast<const int4v_unaligned *>(rows + at + 4 * g)); };
+        int4v q = first_chunk(a.rip, lo[0]);
+        for (int c = cut0; c < cut1; ++c) {
+            load_cut(hi, c + 1);
+            const int base = lane_base - c * (kCutRows * RB);   // tile row 0 is row c * 256 of W
+            const int k_zero = c * kCutRows - 1;
+#pragma unroll
+            for (int j = 0; j < NCW; ++j) {
+                int4v qn = first_chunk(a.rin, lo[2 * j + 1]);
+                run_slice<false>(acc[j], q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
+                // behind the last column: the first slice of the next block starts where this block's ended
+                q = first_chunk(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
+                run_slice<true>(acc[j], qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
+            }
+#pragma unroll
+            for (int i = 0; i < 2 * NCW; ++i) lo[i] = hi[i];
+            if (c + 1 == cut1) break;
+            // exchange the tile (as in the large-M kernel: requests before the barrier, copies behind it)
+            stage_load(c + 1);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            stage_store();
+            __syncthreads();
+        }
+    }
+
+    // partial sums of the four lane groups -> totals in every lane (fixed order: (g0 + g1) + (g2 + g3))
+#pragma unroll
+    for (int j = 0; j < NCW; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float v = acc[j][i];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            acc[j][i] = v;
+        }
+
+    if (a.k_slices > 1) {
+        // this K slice's partial tile for k_reduce, [column][row]: group 0 stores 64 contiguous floats per column
+        constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
+        float *dst = a.partials + ((size_t)cg * a.k_slices + slice) * kTileFloats + (size_t)(wave * NCW) * TM + r * 4;
+        if (g == 0) {
+#pragma unroll
+            for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<float4v *>(dst + (size_t)j * TM));
+        }
+        return;
+    }
+
+    // output: Y = acc + b (bias added once, last), then the optional PReLU; lane group g stores row 4 r + g
+    const int m = 4 * r + g;
+    if (m >= M) return;
+    float *yrow = a.Y + (size_t)m * N + c0;
+#pragma unroll
+    for (int j = 0; j < NCW; ++j) {
+        if (c0 + j >= N) continue;
+        const float s = g == 0 ? acc[j][0] : g == 1 ? acc[j][1] : g == 2 ? acc[j][2] : acc[j][3];
+        const float bias = a.b != nullptr ? a.b[c0 + j] : 0.f;
+        yrow[j] = activate(s + bias, a.alpha, a.alpha_stride, c0 + j);
+    }
+}
+
+template <int NCW>
+hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, int k_slices,
+                  hipStream_t stream)
+{
+    const tcsc_layout_t &l = t->layout;
+    const DeviceTcsc d = device_view(t);
+    const int k_pad = l.n_cuts * kCutRows;
+    if ((size_t)k_pad * TM * sizeof(float) > d.xt_capacity) return hipErrorInvalidValue;
+    hipError_t e = launch_pack(X, d.xt, M, l.K, k_pad, TM, stream);
+    if (e != hipSuccess) return e;
+
+    SmallArgs a;
+    a.xt = d.xt; a.cuts = d.list_cuts; a.rip = d.row_index_pos; a.rin = d.row_index_neg;
+    a.b = b; a.alpha = act.alpha; a.alpha_stride = act.alpha_stride; a.Y = Y; a.partials = d.partials;
+    a.M = M; a.N = l.N; a.n_pad = l.n_pad; a.n_cuts = l.n_cuts;
+    a.n_colgroups = l.n_pad / (NW * NCW);
+    if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
+    const size_t slice_bytes = (size_t)a.n_colgroups * NW * NCW * TM * sizeof(float);
+    if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
+    if (k_slices < 1) k_slices = 1;
+    a.k_slices = k_slices;
+    a.cuts_per_slice = (l.n_cuts + k_slices - 1) / k_slices;
+    const long long grid = (long long)a.n_colgroups * k_slices;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
+    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
+    hipLaunchKernelGGL((k_small<NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    e = hipGetLastError();
+    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    if (e != hipSuccess || k_slices == 1) return e;
+    return launch_reduce(NW * NCW, d.partials, b, act, Y, M, l.N, 1, a.n_colgroups, k_slices, TM, stream);
+}
+
+}  // namespace
+
+// M <= 64: one tile.  2 columns per wavefront (1 on request); K sliced (at the list cuts) only as far as it takes to
+// give every compute unit two workgroups.
+hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                        hipStream_t stream)
+{
+    if (M > TM) return hipErrorInvalidValue;
+    const tcsc_layout_t &l = t->layout;
+    const int ncw = g_cols_per_wave == 1 ? 1 : 2;
+    const long long groups = l.n_pad / (NW * ncw);
+    int k_slices = g_k_slices;
+    if (k_slices == 0) {
+        const int slots = 2 * compute_units();
+        k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
+        if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
+    }
+    if (k_slices > l.n_cuts) k_slices = l.n_cuts;
+    return ncw == 1 ? launch<1>(X, t, b, act, Y, M, k_slices, stream) : launch<2>(X, t, b, act, Y, M, k_slices, stream);
+}
+
+}  // namespace tst

@@ -66,4 +66,14 @@ def decode_device_form(t):
         W[r::64][(masks[:, :lay.N, 1] & bit) != 0] = -1
     assert not W[lay.K:].any()                                # no row at or beyond K
     W = W[:lay.K]
+    # list cuts: entry [c][n] = number of the first entry of column n's list whose row is >= 256 c (plain search here)
+    assert lay.n_cuts == -(-lay.K // 256)
+    cuts = view(lay.off_list_cuts, (lay.n_cuts + 1) * lay.n_pad * 2, np.int32).reshape(lay.n_cuts + 1, lay.n_pad, 2)
+    assert not cuts[:, lay.N:, :].any()
+    for sign, (cs, ri) in enumerate(((canon[0], canon[2]), (canon[1], canon[3]))):
+        for n in range(lay.N):
+            col = ri[cs[n]:cs[n + 1]]
+            expect = cs[n] + np.searchsorted(col, 256 * np.arange(lay.n_cuts + 1), side="left")
+            assert np.array_equal(cuts[:, n, sign], expect), (sign, n)
+            assert cuts[lay.n_cuts, n, sign] == cs[n + 1]
     return W, canon

@@ -17,7 +17,7 @@ SHAPES = [(1, 1, 1), (3, 37, 5), (2, 513, 65), (8, 64, 1), (5, 130, 9), (9, 37, 
 
 
 @pytest.mark.parametrize("K,N,density", [(37, 5, 0.5), (513, 65, 0.5), (512, 512, 0.5), (1000, 130, 0.0625),
-                                         (64, 9, 1.0), (130, 70, 0.0)])
+                                         (64, 9, 1.0), (130, 70, 0.0), (256, 3, 1.0), (2049, 20, 0.25)])
 def test_reblocked_streams_decode_to_w(K, N, density):
     W, _, _ = si.make_inputs(1, K, N, density, "uniform", seed=200 + K + N)
     t = tg.tcsc_upload(tg.tcsc_build(W))
@@ -155,7 +155,29 @@ def test_launch_shapes(cols_per_wave, k_slices):
         tg.tstgemm_set_tuning(0, 0, 0)
 
 
-@pytest.mark.parametrize("M,K,N", [(70, 130, 67), (300, 516, 100), (6, 130, 40)])
+@pytest.mark.parametrize("cols_per_wave", [0, 1])
+@pytest.mark.parametrize("k_slices", [0, 1, 3, 8])
+@pytest.mark.parametrize("M,K,N,density", [(64, 1100, 200, 0.5), (33, 257, 70, 0.5), (9, 2100, 40, 0.0625),
+                                           (50, 600, 130, 1.0), (16, 256, 64, 0.25)])
+def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density):
+    """The path for 8 < M <= 64 (one tile of 64 rows, lists cut every 256 rows of W): lists shorter and longer than
+    one 16-entry step, empty slices, K below, at and above the cut size, with and without K slices."""
+    W, X, b = si.make_inputs(M, K, N, density, "normal", seed=61 + M)
+    _, Xi, _ = si.make_inputs(M, K, N, density, "int8", seed=62 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, b)
+    try:
+        tg.tstgemm_set_tuning(cols_per_wave, k_slices, 0)
+        Y, h = gpu_tstgemm(W, X, b)
+        assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices}")
+        Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+        assert np.array_equal(Yi, Ydi.astype(np.float32))
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+
+
+@pytest.mark.parametrize("M,K,N", [(70, 130, 67), (300, 516, 100), (6, 130, 40), (40, 130, 67)])
 def test_unaligned_operands(M, K, N):
     """X, b and Y that start 4 bytes off a 16-byte boundary (views into larger tensors): the element-wise paths."""
     import torch
