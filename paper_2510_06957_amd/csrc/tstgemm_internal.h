@@ -13,7 +13,7 @@ namespace tst {
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
 constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
-constexpr int kIndexSlack = 16;   // entries behind each index array that may be read (never used)
+constexpr int kIndexSlack = 32;   // entries behind each index array that may be read (never used)
 constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: [k_slices][padded rows][n_pad] fp32
 constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
 
@@ -79,7 +79,8 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
 // tstgemm_side.hip -- X packing pre-pass and split-K reduction, shared by the tiled paths.
 constexpr int kMaxKSlices = 8;
 int compute_units();
-// X (rows x K, row-major) -> xt[tile][k_pad][TM] (TM = 64, 128 or 256 rows per tile, k_pad a multiple of 64), zero padded.
+// X (rows x K, row-major) -> xt[tile][k_pad][TM] (TM = 64, 128 or 256 rows per tile, or one tile of 32; k_pad a
+// multiple of 64), zero padded.
 hipError_t launch_pack(const float *X, float *xt, int rows, int K, int k_pad, int TM, hipStream_t stream);
 // Y = sum of the k_slices partial tiles ([tile][slice][C columns][TM rows], C = 16, 32 or 64) in slice order + b, then act.
 hipError_t launch_reduce(int C, const float *partials, const float *b, const Activation &act, float *Y, int M, int N,

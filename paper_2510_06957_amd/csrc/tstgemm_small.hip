@@ -4,19 +4,20 @@
 // the end; no multiplications.  With at most 64 rows of X a wavefront has more lanes than rows, so the mapping
 // differs from the large-M kernel's:
 //
-//   * the 64 lanes form 4 groups of 16; a lane owns 4 consecutive rows of X, a group all 64 rows of the tile;
-//   * the four groups take four consecutive members of the SAME list at a time (the paper's "horizontal" scheme,
-//     Sec. 3, between the groups; its "vertical" scheme inside a group): one ds_read_b128 of the wavefront gathers
-//     four tile rows, one per group, and every group keeps its own partial sums, which are added across the groups
-//     once, at the end of the K slice (a fixed order);
+//   * the 64 lanes form G groups (G = 4 for M <= 64, 8 for M <= 32); a lane owns 4 consecutive rows of X, a group all
+//     TM = 256 / G rows of the tile;
+//   * the G groups take G consecutive members of the SAME list at a time (the paper's "horizontal" scheme, Sec. 3,
+//     between the groups; its "vertical" scheme inside a group): one ds_read_b128 of the wavefront gathers G tile
+//     rows, one per group, and every group keeps its own partial sums, which are added across the groups once, at the
+//     end of the K slice (a fixed order);
 //   * the members come straight from the TCSC arrays (Sec. 2): the lists are ascending, so the piece of a list that
-//     falls into a block of 256 rows of W (the paper's blocking, Sec. 3) is a slice of row_index_pos / _neg; the
-//     re-blocking pass stores where the slices start (list_cuts).  A lane loads 4 consecutive row numbers with one
-//     16-byte load, 16 per wavefront, one load ahead of their use; a row number costs one VALU instruction (shift
-//     and add to the lane's LDS address) and no scalar work;
-//   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of 256 rows of the packed X tile in the LDS
-//     (64 KiB, tile[k][64 rows]) with a row of zeros in front of it for the slots behind the end of a slice; two
-//     workgroups share a compute unit, one computes while the other exchanges its tile;
+//     falls into a block of rows of W (the paper's blocking, Sec. 3) is a slice of row_index_pos / _neg; the
+//     re-blocking pass stores where the slices start (list_cuts, a cut every 256 rows).  A lane loads 4 consecutive
+//     row numbers with one 16-byte load, 4 G per wavefront, one load ahead of their use; a row number costs one VALU
+//     instruction (shift and add to the lane's LDS address) and no scalar work;
+//   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of the packed X tile in the LDS (64 KiB:
+//     256 rows of W at TM = 64, 512 at TM = 32; tile[k][TM]) with a row of zeros in front of it for the slots behind
+//     the end of a slice; two workgroups share a compute unit, one computes while the other exchanges its tile;
 //   * split K, packing pre-pass and reduction as in the large-M path.
 #include "tstgemm_internal.h"
 
@@ -25,63 +26,73 @@ namespace {
 
 constexpr int NW = 16;        // wavefronts per workgroup
 constexpr int NT = NW * 64;   // threads per workgroup
-constexpr int TM = 64;        // rows of X per tile
-constexpr int RB = TM * 4;    // bytes of a tile row
-constexpr int STAGE = kCutRows * RB;          // bytes of one block of the tile (64 KiB)
+constexpr int STAGE = 65536;                  // bytes of one block of the tile
 constexpr int LPT = STAGE / (NT * 16);        // 16-byte pieces per thread and block
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int4v int4v_unaligned __attribute__((aligned(4)));   // the lists start at any entry: 4-byte aligned 16-byte loads
 typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;   // read through the scalar cache
+typedef const __attribute__((address_space(3))) float4v *lds_f4_ptr;
+
+// Geometry for G lane groups.
+template <int G> struct Geo {
+    static constexpr int L = 64 / G;            // lanes per group
+    static constexpr int TM = 4 * L;            // rows of X per tile
+    static constexpr int RB = TM * 4;           // bytes of a tile row
+    static constexpr int SH = G == 4 ? 8 : 7;   // log2(RB)
+    static constexpr int ROWS = STAGE / RB;     // rows of W per block
+    static constexpr int CUTS = ROWS / kCutRows;   // list cuts per block
+    static constexpr int CH = 4 * G;            // list entries per wavefront and step
+    static_assert((1 << SH) == RB && CH <= kIndexSlack, "geometry");
+};
 
 struct SmallArgs {
-    const float *xt;            // xt[k_pad][64]: the one tile of X, packed
+    const float *xt;            // xt[k_pad][TM]: the one tile of X, packed
     const int32_t *cuts;        // [n_cuts + 1][n_pad][2]
     const int32_t *rip, *rin;   // row_index_pos / row_index_neg
     const float *b;
     const float *alpha;
     float *Y;
-    float *partials;            // [colgroup][k_slices][16 NCW columns][64 rows] when k_slices > 1
-    int M, N, n_pad, n_cuts, n_colgroups, k_slices, cuts_per_slice;
+    float *partials;            // [colgroup][k_slices][16 NCW columns][TM rows] when k_slices > 1
+    int M, N, n_pad, n_cuts, n_blocks, n_colgroups, k_slices, blocks_per_slice;
     int remap, alpha_stride;
 };
 
 // Four gathers of the wavefront: tile rows k[0..3] (per lane group), this lane's four X rows of each.  base is the
 // lane's LDS address of row 0 of the W block minus the block's first row times the row size, so that
-// address = (row number << 8) + base needs no subtraction.
-typedef const __attribute__((address_space(3))) float4v *lds_f4_ptr;
-__device__ __forceinline__ void gather4(float4v (&v)[4], const int4v &k, int base)
+// address = (row number << SH) + base needs no subtraction.
+template <int SH> __device__ __forceinline__ void gather4(float4v (&v)[4], const int4v &k, int base)
 {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) v[t] = *reinterpret_cast<lds_f4_ptr>((k[t] << 8) + base);
+    for (int t = 0; t < 4; ++t) v[t] = *reinterpret_cast<lds_f4_ptr>((k[t] << SH) + base);
 }
 
-// The slice rows[lo .. hi) of a list: lane group g takes entries 16 c + 4 g .. + 3 of chunk c; q holds the lane's
-// entries of chunk 0 (loaded by the caller, one slice ahead).  Entries behind hi (up to 15 are loaded beyond the end
-// of a slice; the index arrays have that much slack) are replaced by k_zero, the row in front of the block, which
-// holds zeros.
-template <bool NEG>
+// A slice of n entries of a list: lane group g takes entries CH c + 4 g .. + 3 of step c; p points at the lane's
+// entries of step 0 and q holds them (loaded by the caller, one slice ahead).  Entries behind the end of the slice
+// (up to CH - 1 are loaded beyond it; the index arrays have that much slack) are replaced by k_zero, the row in
+// front of the block, which holds zeros.
+template <int G, bool NEG>
 __device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *__restrict__ p, int n, int base,
                                           int k_zero, int g)
 {
-    // p = rows + lo + 4 g
-    for (int c = 16; c <= n; c += 16) {
+    constexpr int CH = Geo<G>::CH, SH = Geo<G>::SH;
+    for (int c = CH; c <= n; c += CH) {
         const int4v cur = q;
         q = *reinterpret_cast<const int4v_unaligned *>(p + c);
         float4v v[4];
-        gather4(v, cur, base);
+        gather4<SH>(v, cur, base);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if constexpr (NEG) acc -= v[t]; else acc += v[t];
         }
     }
-    const int rem = n & 15;
+    const int rem = n & (CH - 1);
     if (n > 0 && rem) {
         int4v cur;
 #pragma unroll
         for (int t = 0; t < 4; ++t) cur[t] = (4 * g + t < rem) ? q[t] : k_zero;
         float4v v[4];
-        gather4(v, cur, base);
+        gather4<SH>(v, cur, base);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if constexpr (NEG) acc -= v[t]; else acc += v[t];
@@ -89,27 +100,29 @@ __device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *
     }
 }
 
-template <int NCW>
+template <int NCW, int G>
 __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 {
-    __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then tile rows 0 .. 255
+    using geo = Geo<G>;
+    constexpr int L = geo::L, TM = geo::TM, RB = geo::RB;
+    __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then the rows of the block
     char *const tile = lds + RB;
     const int M = a.M, N = a.N;
-    const int lane = threadIdx.x & 63, g = lane >> 4, r = lane & 15;
+    const int lane = threadIdx.x & 63, g = lane / L, r = lane % L;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     int wg = blockIdx.x;
     if (a.remap) wg = (wg & 7) * a.remap + (wg >> 3);
     const int cg = wg % a.n_colgroups, slice = wg / a.n_colgroups;
     const int c0 = (cg * NW + wave) * NCW;   // < n_pad by construction of the grid
-    const int cut0 = min(slice * a.cuts_per_slice, a.n_cuts);
-    const int cut1 = min(cut0 + a.cuts_per_slice, a.n_cuts);
+    const int blk0 = min(slice * a.blocks_per_slice, a.n_blocks);
+    const int blk1 = min(blk0 + a.blocks_per_slice, a.n_blocks);
 
     float4v acc[NCW];
 #pragma unroll
     for (int j = 0; j < NCW; ++j) acc[j] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    if (cut0 < cut1) {
+    if (blk0 < blk1) {
         const char *xtile = reinterpret_cast<const char *>(a.xt);
         const int piece = threadIdx.x * 16;
         float4v st[LPT];
@@ -122,41 +135,44 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 #pragma unroll
             for (int i = 0; i < LPT; ++i) *reinterpret_cast<float4v *>(tile + piece + i * NT * 16) = st[i];
         };
-        // slice borders of (cut, c0 .. c0+NCW-1): 2 NCW consecutive ints per cut (column j: +1 list, -1 list)
+        // slice borders of (block, c0 .. c0+NCW-1): 2 NCW consecutive ints per cut (column j: +1 list, -1 list)
         const const_i32_ptr cuts_base =
             reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(a.cuts)) + (size_t)c0 * 2;
         const size_t cuts_stride = (size_t)a.n_pad * 2;
         int lo[2 * NCW], hi[2 * NCW];
-        auto load_cut = [&](int (&dst)[2 * NCW], int c) {
+        auto load_cut = [&](int (&dst)[2 * NCW], int blk) {
+            const int cut = min(blk * geo::CUTS, a.n_cuts);   // the last block may end early: the end of the lists
 #pragma unroll
-            for (int i = 0; i < 2 * NCW; ++i) dst[i] = cuts_base[(size_t)c * cuts_stride + i];
+            for (int i = 0; i < 2 * NCW; ++i) dst[i] = cuts_base[(size_t)cut * cuts_stride + i];
         };
 
         if (threadIdx.x < RB / 4) reinterpret_cast<float *>(lds)[threadIdx.x] = 0.f;
-        load_cut(lo, cut0);
-        stage_load(cut0);
+        load_cut(lo, blk0);
+        stage_load(blk0);
         stage_store();
         __syncthreads();
         const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         const int lane_base = lds0 + RB + r * 16;     // this lane's part of tile row 0
-        // first chunk of a slice: this lane's 4 entries, loaded one slice ahead of their use
-        auto first_chunk = [&](const int32_t *rows, int at) { return int4v(*reinterpret_cast<const int4v_unaligned *>(rows + at + 4 * g)); };
-        int4v q = first_chunk(a.rip, lo[0]);
-        for (int c = cut0; c < cut1; ++c) {
+        // first step of a slice: this lane's 4 entries, loaded one slice ahead of their use
+        auto first_step = [&](const int32_t *rows, int at) {
+            return int4v(*reinterpret_cast<const int4v_unaligned *>(rows + at + 4 * g));
+        };
+        int4v q = first_step(a.rip, lo[0]);
+        for (int c = blk0; c < blk1; ++c) {
             load_cut(hi, c + 1);
-            const int base = lane_base - c * (kCutRows * RB);   // tile row 0 is row c * 256 of W
-            const int k_zero = c * kCutRows - 1;
+            const int base = lane_base - c * STAGE;   // tile row 0 is row c * ROWS of W
+            const int k_zero = c * geo::ROWS - 1;
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                int4v qn = first_chunk(a.rin, lo[2 * j + 1]);
-                run_slice<false>(acc[j], q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
+                int4v qn = first_step(a.rin, lo[2 * j + 1]);
+                run_slice<G, false>(acc[j], q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
                 // behind the last column: the first slice of the next block starts where this block's ended
-                q = first_chunk(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
-                run_slice<true>(acc[j], qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
+                q = first_step(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
+                run_slice<G, true>(acc[j], qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
             }
 #pragma unroll
             for (int i = 0; i < 2 * NCW; ++i) lo[i] = hi[i];
-            if (c + 1 == cut1) break;
+            if (c + 1 == blk1) break;
             // exchange the tile (as in the large-M kernel: requests before the barrier, copies behind it)
             stage_load(c + 1);
             asm volatile("" ::: "memory");
@@ -167,19 +183,19 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
         }
     }
 
-    // partial sums of the four lane groups -> totals in every lane (fixed order: (g0 + g1) + (g2 + g3))
+    // partial sums of the lane groups -> totals in every lane (a fixed tree over the groups)
 #pragma unroll
     for (int j = 0; j < NCW; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float v = acc[j][i];
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
+#pragma unroll
+            for (int d = L; d < 64; d <<= 1) v += __shfl_xor(v, d, 64);
             acc[j][i] = v;
         }
 
     if (a.k_slices > 1) {
-        // this K slice's partial tile for k_reduce, [column][row]: group 0 stores 64 contiguous floats per column
+        // this K slice's partial tile for k_reduce, [column][row]: group 0 stores TM contiguous floats per column
         constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
         float *dst = a.partials + ((size_t)cg * a.k_slices + slice) * kTileFloats + (size_t)(wave * NCW) * TM + r * 4;
         if (g == 0) {
@@ -189,9 +205,9 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
         return;
     }
 
-    // output: Y = acc + b (bias added once, last), then the optional PReLU; lane group g stores row 4 r + g
+    // output: Y = acc + b (bias added once, last), then the optional PReLU; lane group g < 4 stores row 4 r + g
     const int m = 4 * r + g;
-    if (m >= M) return;
+    if (g >= 4 || m >= M) return;
     float *yrow = a.Y + (size_t)m * N + c0;
 #pragma unroll
     for (int j = 0; j < NCW; ++j) {
@@ -202,33 +218,37 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
     }
 }
 
-template <int NCW>
+template <int NCW, int G>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, int k_slices,
                   hipStream_t stream)
 {
+    using geo = Geo<G>;
+    constexpr int TM = geo::TM;
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
-    const int k_pad = l.n_cuts * kCutRows;
-    if ((size_t)k_pad * TM * sizeof(float) > d.xt_capacity) return hipErrorInvalidValue;
+    const int n_blocks = (l.K + geo::ROWS - 1) / geo::ROWS;
+    const int k_pad = n_blocks * geo::ROWS;
+    if ((size_t)k_pad * TM * sizeof(float) > d.xt_capacity || M > TM) return hipErrorInvalidValue;
     hipError_t e = launch_pack(X, d.xt, M, l.K, k_pad, TM, stream);
     if (e != hipSuccess) return e;
 
     SmallArgs a;
     a.xt = d.xt; a.cuts = d.list_cuts; a.rip = d.row_index_pos; a.rin = d.row_index_neg;
     a.b = b; a.alpha = act.alpha; a.alpha_stride = act.alpha_stride; a.Y = Y; a.partials = d.partials;
-    a.M = M; a.N = l.N; a.n_pad = l.n_pad; a.n_cuts = l.n_cuts;
+    a.M = M; a.N = l.N; a.n_pad = l.n_pad; a.n_cuts = l.n_cuts; a.n_blocks = n_blocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
+    if (k_slices > n_blocks) k_slices = n_blocks;
     if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
     const size_t slice_bytes = (size_t)a.n_colgroups * NW * NCW * TM * sizeof(float);
     if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
-    a.cuts_per_slice = (l.n_cuts + k_slices - 1) / k_slices;
+    a.blocks_per_slice = (n_blocks + k_slices - 1) / k_slices;
     const long long grid = (long long)a.n_colgroups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_small<NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL((k_small<NCW, G>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
@@ -237,23 +257,26 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
 
 }  // namespace
 
-// M <= 64: one tile.  2 columns per wavefront (1 on request); K sliced (at the list cuts) only as far as it takes to
-// give every compute unit two workgroups.
+// M <= 64: one tile of 64 rows, or of 32 rows with twice as many rows of W per block.  Two columns per wavefront and
+// K sliced (at block borders) as far as it takes to give every compute unit two workgroups; a short K (at most four
+// list cuts) is not sliced and takes one column per wavefront instead, which saves the reduction kernel.
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream)
 {
-    if (M > TM) return hipErrorInvalidValue;
+    if (M > 64) return hipErrorInvalidValue;
     const tcsc_layout_t &l = t->layout;
-    const int ncw = g_cols_per_wave == 1 ? 1 : 2;
+    const bool short_k = l.n_cuts <= 4;
+    const int ncw = g_cols_per_wave ? (g_cols_per_wave == 1 ? 1 : 2) : (short_k ? 1 : 2);
     const long long groups = l.n_pad / (NW * ncw);
     int k_slices = g_k_slices;
     if (k_slices == 0) {
         const int slots = 2 * compute_units();
-        k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
-        if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
+        k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
     }
-    if (k_slices > l.n_cuts) k_slices = l.n_cuts;
-    return ncw == 1 ? launch<1>(X, t, b, act, Y, M, k_slices, stream) : launch<2>(X, t, b, act, Y, M, k_slices, stream);
+    if (M <= 32)
+        return ncw == 1 ? launch<1, 8>(X, t, b, act, Y, M, k_slices, stream)
+                        : launch<2, 8>(X, t, b, act, Y, M, k_slices, stream);
+    return ncw == 1 ? launch<1, 4>(X, t, b, act, Y, M, k_slices, stream) : launch<2, 4>(X, t, b, act, Y, M, k_slices, stream);
 }
 
 }  // namespace tst

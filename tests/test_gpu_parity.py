@@ -158,10 +158,12 @@ def test_launch_shapes(cols_per_wave, k_slices):
 @pytest.mark.parametrize("cols_per_wave", [0, 1])
 @pytest.mark.parametrize("k_slices", [0, 1, 3, 8])
 @pytest.mark.parametrize("M,K,N,density", [(64, 1100, 200, 0.5), (33, 257, 70, 0.5), (9, 2100, 40, 0.0625),
-                                           (50, 600, 130, 1.0), (16, 256, 64, 0.25)])
+                                           (50, 600, 130, 1.0), (16, 256, 64, 0.25), (32, 1100, 100, 0.5),
+                                           (20, 513, 40, 0.25), (31, 1536, 64, 1.0)])
 def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density):
-    """The path for 8 < M <= 64 (one tile of 64 rows, lists cut every 256 rows of W): lists shorter and longer than
-    one 16-entry step, empty slices, K below, at and above the cut size, with and without K slices."""
+    """The path for 8 < M <= 64 (one tile of 64 rows with blocks of 256 rows of W, or of 32 rows with blocks of 512):
+    lists shorter and longer than one step of the wavefront, empty slices, K below, at and above the block size, a
+    last block that ends early, with and without K slices."""
     W, X, b = si.make_inputs(M, K, N, density, "normal", seed=61 + M)
     _, Xi, _ = si.make_inputs(M, K, N, density, "int8", seed=62 + M)
     ot = oracle.tcsc_build(W)
