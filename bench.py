@@ -142,7 +142,8 @@ def main():
     torch.cuda.synchronize()
     kernel_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
 
-    decode = wl.M <= 8   # the library's rule for its small-M kernel
+    decode = wl.M <= 8          # the library's rules for its decode kernel ...
+    small = 8 < wl.M <= 64      # ... and its small-tile kernel
     traffic = MEASURED_TRAFFIC.get(wl.name)
     if decode:
         # small-M path streams the four TCSC arrays once: index-bandwidth bound
@@ -150,15 +151,17 @@ def main():
         roof = {"bound": "hbm", "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "traffic": traffic}
     else:
-        # index data the kernel reads (64-bit row sets) + X + Y + b
-        alg_bytes = 16 * lay.n_kblocks * lay.n_pad + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
+        # index data the kernel reads (small tile: the TCSC row numbers and the list cuts; else the 64-bit row sets)
+        # + X + Y + b
+        index_bytes = (4 * nnz + 8 * (lay.n_cuts + 1) * lay.n_pad) if small else 16 * lay.n_kblocks * lay.n_pad
+        alg_bytes = index_bytes + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
         roof = {"bound": "lds", "achieved": adds / (kernel_ms * 1e-3) / 1e12, "peak": PEAK_LDS_GATHER_TFLOPS,
                 "unit": "TFLOP/s", "traffic": traffic,
                 "note": "1 flop = 1 fp32 add = one 4-byte LDS gather; peak = LDS read port, 256 B/clk/CU x 256 CUs x "
                         "2.4 GHz; the fp32 add rate of the vector ALUs (alu_add_peak) is twice that",
                 "alu_add_peak": PEAK_ALU_ADD_TFLOPS}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = "k_decode" if decode else "k_large"
+    roof["kernel"] = "k_decode" if decode else "k_small" if small else "k_large"
     roof["kernel_ms"] = kernel_ms
     roof["algorithmic_adds_per_launch"] = adds
     roof["algorithmic_bytes_per_launch"] = alg_bytes
@@ -177,7 +180,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: M={wl.M} K={wl.K} N={wl.N} density={wl.density} X,b~{wl.dist} "
                                f"seed={wl.seed}", "nnz": nnz,
-                   "index_type": "int32 TCSC in, 64-bit row sets per K-block on device",
+                   "index_type": "int32 TCSC in; on device the TCSC arrays (M <= 64) or 64-bit row sets per K-block",
                    "tcsc_build_ms_host": build_ms, "upload_and_reblock_ms": upload_ms},
         "roofline": roof,
     }

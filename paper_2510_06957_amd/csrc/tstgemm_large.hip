@@ -1,12 +1,12 @@
-// Large-M kernels of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper) for gfx950.
+// Large-M kernel (M > 64) of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper) for gfx950.
 //
 // Arithmetic is that of BaseTCSC (Sec. 2): every output is a sum of gathered X entries
 // (+1 list) minus a sum of gathered X entries (-1 list), bias added once at the end; no
 // multiplications.  The mapping to the machine is this library's own:
 //
-//   * k_pack_x copies X into the workspace as row tiles, transposed: xt[tile][k][row], a tile
-//     being TM = 64 R consecutive rows of X (R = 1, 2 or 4), K padded to whole K-blocks, rows
-//     beyond M and entries beyond K zero.  A K-block of a tile (64 x TM floats) is then one
+//   * a pre-pass (k_pack_x, tstgemm_side.hip) copies X into the workspace as row tiles, transposed:
+//     xt[tile][k][row], a tile being TM = 64 R consecutive rows of X (R = 2 or 4), K padded to whole
+//     K-blocks, rows beyond M and entries beyond K zero.  A K-block of a tile (64 x TM floats) is then one
 //     contiguous piece of memory that goes into the LDS with plain 16-byte copies, and the
 //     strided walk over the rows of X happens once per call instead of once per workgroup;
 //   * in k_large one lane owns R consecutive rows of X, a wavefront therefore owns a whole tile,
@@ -30,7 +30,7 @@
 //     the store are fused;
 //   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
 //     8 slices handled by different workgroups; each writes its partial sums to the workspace,
-//     past the caches, and k_reduce adds the slices in slice order, adds the bias and stores Y
+//     past the caches, and k_reduce (tstgemm_side.hip) adds the slices in slice order, adds the bias and stores Y
 //     -- a fixed summation order, so results do not depend on timing, and no atomics or fences.
 #include "tstgemm_internal.h"
 
@@ -363,7 +363,6 @@ hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation 
 hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream)
 {
-    if (M <= 64) return pick<1>(X, t, b, act, Y, M, stream);
     if (M <= 128) return pick<2>(X, t, b, act, Y, M, stream);
     return pick<4>(X, t, b, act, Y, M, stream);
 }

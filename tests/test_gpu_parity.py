@@ -218,11 +218,12 @@ def test_profile_events_bracket_the_main_kernel():
     assert_close(Y.cpu().numpy(), Yd, A, "C1 with events")
 
 
-@pytest.mark.parametrize("M,K,N", [(1, 300, 70), (8, 513, 65), (40, 700, 130), (200, 640, 96), (300, 1000, 200)])
+@pytest.mark.parametrize("M,K,N", [(1, 300, 70), (8, 513, 65), (40, 700, 130), (40, 2100, 130), (20, 1100, 70),
+                                   (200, 640, 96), (300, 1000, 200)])
 @pytest.mark.parametrize("per_column", [False, True])
 def test_prelu_epilogue(M, K, N, per_column):
-    """The fused PReLU (after the bias add) in the decode kernel, the large-M kernel and the split-K reduction kernel,
-    against the oracle's; integer inputs with power-of-two slopes bit for bit."""
+    """The fused PReLU (after the bias add) in the decode kernel, the small-tile and large-M kernels and the split-K
+    reduction kernel, against the oracle's; integer inputs with power-of-two slopes bit for bit."""
     W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=61 + M)
     rng = np.random.default_rng(62)
     alpha = rng.uniform(-1.5, 2.5, N).astype(np.float32) if per_column else np.array([0.25], np.float32)
