@@ -71,8 +71,9 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
 
 /*
  * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
- * the four TCSC arrays unchanged (read by the small-M kernel), their K-blocked form (read by
- * the large-M kernel) and the workspace of tstgemm().  K-blocking follows the idea
+ * the four TCSC arrays unchanged (read by the small-M and small-tile kernels; each index array is
+ * followed by 32 entries of slack, which those kernels may load but never use), their K-blocked
+ * form (read by the large-M kernel) and the workspace of tstgemm().  K-blocking follows the idea
  * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block = 64 rows
  * so that all X entries one block touches fit in the LDS, every column's two lists are cut at
  * the block borders, and the pieces are stored block after block.  A piece holds at most 64
@@ -117,8 +118,10 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * X: DEVICE fp32 M*K row-major.  b: DEVICE fp32 N, or NULL for b = 0.  Y: DEVICE fp32 M*N
  * row-major, fully overwritten; must not overlap X, b or the handle's device buffer.
  * M >= 1 arbitrary; K, N must equal the handle's.  M <= 8 takes the small-M kernel (X resident in the LDS, in
- * chunks of K if it is larger than 150 KiB; TCSC lists streamed), everything else the large-M path.  Asynchronous: the kernels are enqueued on
- * `stream` (a hipStream_t, NULL = null stream), no host synchronisation, no allocation.
+ * chunks of K if it is larger than 150 KiB; TCSC lists streamed), 8 < M <= 64 the small-tile kernel (one tile of
+ * X, lists read from the TCSC arrays between the list cuts), everything else the large-M path (row sets).
+ * Asynchronous: the kernels are enqueued on `stream` (a hipStream_t, NULL = null stream), no host
+ * synchronisation, no allocation.
  * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, EHIP (launch failure).
  * Rounding: fp32 accumulation in an order fixed by (M, K, N), the matrix and the tuning
  * parameters; repeated calls give bit-identical results.  Integer-valued inputs small enough
@@ -142,10 +145,11 @@ int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *
                   int M, int K, int N, void *stream);
 
 /*
- * Launch-shape overrides for the large-M path, for tuning runs and tests: columns per wavefront
- * (1, 2 or 4), number of K slices (1..8) computed by different workgroups and summed in a
- * fixed order, and the largest number of row tiles of X packed and processed at a time
- * (>= 1).  0 restores the built-in choice for that parameter.  Process-wide.
+ * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront
+ * (1, 2 or 4; the small-tile kernel has 1 and 2 and takes 4 as 2), number of K slices (1..8) computed by
+ * different workgroups and summed in a fixed order, and the largest number of row tiles of X packed and
+ * processed at a time (>= 1, large-M path only).  0 restores the built-in choice for that parameter.
+ * Process-wide.
  * Errors: EINVAL for a value outside the ranges above.
  */
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
@@ -153,8 +157,8 @@ int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
 /*
  * For benchmarks that must time one kernel: from now on every tstgemm() call records the
  * hipEvent_t `before` right before and `after` right after the launch of its main kernel
- * (the gather-add kernel; not the packing pre-pass and the split-K reduction of the large-M
- * path), on the call's stream.  Both NULL switches this off (the default).  The events are
+ * (the gather-add kernel; not the packing pre-pass and the split-K reduction of the tiled
+ * paths), on the call's stream.  Both NULL switches this off (the default).  The events are
  * the caller's; a call with more than one slab of rows records them once per slab, so the pair
  * then brackets the last slab only.  Process-wide.  Errors: EINVAL if exactly one is NULL.
  */

@@ -1,7 +1,7 @@
 """CPU oracle for the sparse ternary GEMM Y = X W + b -- TEST INFRASTRUCTURE ONLY.
 
-Thin ctypes loader around oracle/tstgemm_oracle.c (see that file for what it follows in the
-paper).  Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+Thin ctypes loader around oracle/tstgemm_oracle.c and oracle/variants_oracle.c (see those files
+for what they follow in the paper).  Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 package; the product package never does.  It imports nothing from the product package.
 """
 from __future__ import annotations
@@ -27,6 +27,9 @@ def _load():
         lib.oracle_tcsc_count.restype = ctypes.c_int
         lib.oracle_tcsc_to_dense.restype = ctypes.c_int
         lib.oracle_prelu.restype = ctypes.c_int
+        for name in ("oracle_signed_build", "oracle_signed_to_dense", "oracle_tstgemm_signed", "oracle_pack5",
+                     "oracle_unpack5", "oracle_tstgemm_packed"):
+            getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -139,4 +142,94 @@ def prelu(Yd: np.ndarray, A: np.ndarray | None, alpha) -> tuple[np.ndarray, np.n
     rc = _load().oracle_prelu(_p(Yd), _p(A), Yd.shape[0], Yd.shape[1], _p(alpha), int(alpha.size))
     if rc:
         raise ValueError(f"oracle_prelu failed ({rc})")
+    return Yd, A
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# The two alternative encodings of W (Sec. 3, "Inverted Index" and "Value Compression"); see variants_oracle.c.
+
+def signed_build(t: Tcsc) -> tuple[np.ndarray, np.ndarray]:
+    """(col_start, index): the two lists of every column merged, +1 in row i stored as i, -1 as ~i."""
+    col_start = np.empty(t.N + 1, np.int32)
+    index = np.empty(t.nnz, np.int32)
+    rc = _load().oracle_signed_build(_p(t.col_start_pos), _p(t.col_start_neg), _p(t.row_index_pos),
+                                     _p(t.row_index_neg), t.N, _p(col_start), _p(index))
+    if rc:
+        raise ValueError(f"oracle_signed_build failed ({rc})")
+    return col_start, index
+
+
+def signed_to_dense(col_start: np.ndarray, index: np.ndarray, K: int) -> np.ndarray:
+    col_start = np.ascontiguousarray(col_start, dtype=np.int32)
+    index = np.ascontiguousarray(index, dtype=np.int32)
+    N = col_start.size - 1
+    W = np.empty((K, N), np.int8)
+    rc = _load().oracle_signed_to_dense(_p(col_start), _p(index), K, N, _p(W))
+    if rc:
+        raise ValueError(f"oracle_signed_to_dense failed ({rc})")
+    return W
+
+
+def _xb(X, b, K, N):
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    if X.ndim != 2 or X.shape[1] != K:
+        raise ValueError("X has the wrong shape")
+    if b is not None:
+        b = np.ascontiguousarray(b, dtype=np.float32)
+        if b.shape != (N,):
+            raise ValueError("b has the wrong length")
+    return X, b
+
+
+def tstgemm_signed(X, col_start, index, b, K: int):
+    """(Yd, A) of Y = X W + b with W given as merged signed lists."""
+    col_start = np.ascontiguousarray(col_start, dtype=np.int32)
+    index = np.ascontiguousarray(index, dtype=np.int32)
+    N = col_start.size - 1
+    X, b = _xb(X, b, K, N)
+    M = X.shape[0]
+    Yd = np.empty((M, N), np.float64)
+    A = np.empty((M, N), np.float64)
+    rc = _load().oracle_tstgemm_signed(_p(X), _p(col_start), _p(index), _p(b), M, K, N, _p(Yd), _p(A))
+    if rc:
+        raise ValueError(f"oracle_tstgemm_signed failed ({rc})")
+    return Yd, A
+
+
+def pack5(W: np.ndarray) -> np.ndarray:
+    """codes[n][g]: five consecutive rows of column n as one base-3 number (uint8, N x ceil(K/5))."""
+    W = np.ascontiguousarray(W, dtype=np.int8)
+    K, N = W.shape
+    codes = np.empty((N, (K + 4) // 5), np.uint8)
+    rc = _load().oracle_pack5(_p(W), K, N, _p(codes))
+    if rc:
+        raise ValueError(f"oracle_pack5 failed ({rc})")
+    return codes
+
+
+def unpack5(codes: np.ndarray, K: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, G = codes.shape
+    if G != (K + 4) // 5:
+        raise ValueError("codes has the wrong number of groups")
+    W = np.empty((K, N), np.int8)
+    rc = _load().oracle_unpack5(_p(codes), K, N, _p(W))
+    if rc:
+        raise ValueError(f"oracle_unpack5 failed ({rc})")
+    return W
+
+
+def tstgemm_packed(X, codes, b, K: int):
+    """(Yd, A) of Y = X W + b with W given as base-3 codes."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, G = codes.shape
+    if G != (K + 4) // 5:
+        raise ValueError("codes has the wrong number of groups")
+    X, b = _xb(X, b, K, N)
+    M = X.shape[0]
+    Yd = np.empty((M, N), np.float64)
+    A = np.empty((M, N), np.float64)
+    rc = _load().oracle_tstgemm_packed(_p(X), _p(codes), _p(b), M, K, N, _p(Yd), _p(A))
+    if rc:
+        raise ValueError(f"oracle_tstgemm_packed failed ({rc})")
     return Yd, A
