@@ -88,6 +88,16 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *                                             is >= c * 256 (c = n_cuts: the end of the list), [c][n][1]: the same
  *                                             for the -1 list.  Rows ascend inside a list, so the piece of a list
  *                                             inside a block of 256 rows is the slice between two cuts.
+ *   signed_index int32 [nnz_pos + nnz_neg]    the "inverted index" form (Sec. 3): the two lists of a column merged in
+ *                                             ascending row order, +1 in row i stored as i, -1 as ~i; column n's
+ *                                             entries are [col_start_pos[n] + col_start_neg[n],
+ *                                             col_start_pos[n+1] + col_start_neg[n+1]); 32 entries of slack behind it.
+ *                                             Read by tstgemm_signed().
+ *   packed     uint8  [n_chunks5][n_pad][16]  the "value compression" form (Sec. 3): five consecutive rows of a
+ *                                             column in one byte (see tcsc_packed_codes() for the code); group g
+ *                                             of column n is byte [g / 16][n][g % 16], groups beyond ceil(K/5) and
+ *                                             columns >= N hold code 0.  n_chunks5 = ceil(ceil(K/5) / 16).
+ *                                             Read by tstgemm_packed().
  *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): split-K partial sums (32 MiB) and a tiled,
  *                                             transposed copy of (a slab of rows of) X (128 MiB, or one tile of
  *                                             256 rows over the padded K if that is larger)
@@ -95,15 +105,17 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  */
 typedef struct tcsc_layout {
     int32_t K, N, n_pad, k_block, n_kblocks, n_cuts;   /* n_cuts = K / 256 rounded up */
+    int32_t n_chunks5, reserved;
     int64_t nnz_pos, nnz_neg;
     size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
-    size_t off_masks, off_list_cuts, off_workspace, workspace_bytes, total_bytes;
+    size_t off_masks, off_list_cuts, off_signed_index, off_packed, off_workspace, workspace_bytes, total_bytes;
 } tcsc_layout_t;
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);
 
 /*
- * Copy the four arrays to the device and run the GPU re-blocking pass into dev_buf.
+ * Copy the four arrays to the device and run the GPU re-blocking pass (row sets, list cuts, and the
+ * two alternative encodings) into dev_buf.
  * dev_buf: DEVICE, at least tcsc_device_bytes() bytes, 256-byte aligned, owned by the
  * caller; the handle keeps the pointer until tcsc_destroy() and never frees it.  The buffer
  * must stay untouched while the handle is in use.  stream: a hipStream_t (NULL = the null
@@ -143,6 +155,40 @@ int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, in
  */
 int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *alpha, int alpha_count, float *Y,
                   int M, int K, int N, void *stream);
+
+/*
+ * The matrix in the paper's "inverted index" encoding (Sec. 3): one list per column instead of two, +1 in row
+ * i stored as i, -1 in row i as ~i (bitwise NOT), inside a column in ascending row order (the paper does not
+ * state the order; this is the order of the lists that are merged).  col_start: HOST, N+1 entries;
+ * index: HOST, nnz_pos + nnz_neg entries.  Computed on the host from the handle's arrays.
+ */
+int tcsc_signed_arrays(const tcsc_t *t, int32_t *col_start, int32_t *index);
+
+/*
+ * The matrix in the paper's "value compression" encoding (Sec. 3): five ternary entries per byte, the five
+ * being the digits of a base-3 number.  What the paper leaves open is fixed like this: the five are
+ * consecutive rows 5g .. 5g+4 of one column (rows >= K count as 0), an entry 0 / +1 / -1 is the digit 0 / 1 /
+ * 2, the first row is the most significant digit (code = 81 d0 + 27 d1 + 9 d2 + 3 d3 + d4 <= 242), and the
+ * codes are stored column after column.  codes: HOST, N * ceil(K/5) bytes, codes[n * ceil(K/5) + g].
+ */
+int tcsc_packed_codes(const tcsc_t *t, uint8_t *codes);
+
+/*
+ * Y = X W + b for M <= 8 from the inverted-index form in the device buffer (the decode kernel with one
+ * signed list per column: the sign of an entry selects add or subtract, branch-free).  Arguments, rounding
+ * and ordering rules as for tstgemm().  Errors: as tstgemm(), and EINVAL for M > 8.
+ */
+int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
+
+/*
+ * Y = X W + b for M <= 8 from the value-compression form in the device buffer: every byte is decoded
+ * through a 243-entry table (as in the paper) into five weights, and ALL entries take part in the sum,
+ * the zeros as x * 0.  Unlike every other entry point this one therefore reads X entries whose weight is
+ * zero: X must be finite.  Products with -1, 0, +1 are exact, so the rounding is that of the additions,
+ * in an order fixed by (M, K, N).  Arguments otherwise as for tstgemm().  Errors: as tstgemm(), and
+ * EINVAL for M > 8.
+ */
+int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
  * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront

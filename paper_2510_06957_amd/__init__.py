@@ -4,11 +4,12 @@ Python binding of libtstgemm.so: argument marshalling only, every step of the co
 runs in the HIP library.  PyTorch supplies device memory and streams.
 """
 from .binding import (TstgemmError, Tcsc, library_path, tcsc_build, tcsc_from_arrays, tcsc_to_dense, tcsc_dims,
-                      tcsc_arrays, tcsc_device_bytes, tcsc_layout, tcsc_upload, tstgemm, tstgemm_set_tuning, tstgemm_profile_events,
-                      tcsc_destroy,
+                      tcsc_arrays, tcsc_device_bytes, tcsc_layout, tcsc_upload, tstgemm, tstgemm_signed, tstgemm_packed, tcsc_signed_arrays, tcsc_packed_codes,
+                      tstgemm_set_tuning, tstgemm_profile_events, tcsc_destroy,
                       tcsc_strerror)
 
 __all__ = ["TstgemmError", "Tcsc", "library_path", "tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims",
-           "tcsc_arrays", "tcsc_device_bytes", "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_set_tuning", "tstgemm_profile_events",
+           "tcsc_arrays", "tcsc_device_bytes", "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_signed", "tstgemm_packed",
+           "tcsc_signed_arrays", "tcsc_packed_codes", "tstgemm_set_tuning", "tstgemm_profile_events",
            "tcsc_destroy",
            "tcsc_strerror"]

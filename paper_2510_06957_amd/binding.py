@@ -24,10 +24,12 @@ class TstgemmError(RuntimeError):
 class TcscLayout(ctypes.Structure):
     _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("n_pad", ctypes.c_int32), ("k_block", ctypes.c_int32),
                 ("n_kblocks", ctypes.c_int32), ("n_cuts", ctypes.c_int32),
+                ("n_chunks5", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("nnz_pos", ctypes.c_int64), ("nnz_neg", ctypes.c_int64),
                 ("off_col_start_pos", ctypes.c_size_t), ("off_col_start_neg", ctypes.c_size_t),
                 ("off_row_index_pos", ctypes.c_size_t), ("off_row_index_neg", ctypes.c_size_t),
-                ("off_masks", ctypes.c_size_t), ("off_list_cuts", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
+                ("off_masks", ctypes.c_size_t), ("off_list_cuts", ctypes.c_size_t),
+                ("off_signed_index", ctypes.c_size_t), ("off_packed", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
                 ("workspace_bytes", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
 
 
@@ -59,6 +61,10 @@ def _load():
     lib.tcsc_upload.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tstgemm.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
     lib.tstgemm_prelu.argtypes = [vp, vp, vp, vp, ci, vp, ci, ci, ci, vp]
+    lib.tstgemm_signed.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.tstgemm_packed.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.tcsc_signed_arrays.argtypes = [vp, vp, vp]
+    lib.tcsc_packed_codes.argtypes = [vp, vp]
     lib.tcsc_destroy.argtypes = [vp]
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
@@ -68,7 +74,8 @@ def _load():
     lib.tstgemm_profile_events.argtypes = [vp, vp]
     lib.tstgemm_profile_events.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-                 "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu"):
+                 "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_signed", "tstgemm_packed",
+                 "tcsc_signed_arrays", "tcsc_packed_codes"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -195,12 +202,8 @@ def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
     return t
 
 
-def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
-    """Y = X W + b on the GPU, or Y = PReLU(X W + b) when `alpha` is given (tstgemm_prelu of the C ABI).
-    X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None; alpha: cuda float32 with 1 or N entries.
-
-    Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
-    handle was uploaded to and the one holding X, b, alpha and Y."""
+def _gemm_args(X, t: Tcsc, b, Y):
+    """Checks shared by the tstgemm* wrappers; returns (M, K, N, b_ptr, Y)."""
     import torch
     f32 = torch.float32
     if not (X.is_cuda and X.dtype == f32 and X.dim() == 2 and X.is_contiguous()):
@@ -216,14 +219,25 @@ def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
         b_ptr = b.data_ptr()
     else:
         raise ValueError("b must be a contiguous float32 CUDA vector of length N on X's device")
-    if alpha is not None and not (alpha.is_cuda and alpha.dtype == f32 and alpha.is_contiguous()
-                                  and alpha.numel() in (1, N) and alpha.device.index == dev):
-        raise ValueError("alpha must be a contiguous float32 CUDA tensor with 1 or N entries on X's device")
     if Y is None:
         Y = torch.empty((M, N), dtype=f32, device=X.device)
     elif not (Y.is_cuda and Y.dtype == f32 and Y.dim() == 2 and Y.shape[0] == M and Y.shape[1] == N
               and Y.is_contiguous() and Y.device.index == dev):
         raise ValueError("Y must be a contiguous float32 CUDA matrix of shape [M, N] on X's device")
+    return M, K, N, b_ptr, Y
+
+
+def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
+    """Y = X W + b on the GPU, or Y = PReLU(X W + b) when `alpha` is given (tstgemm_prelu of the C ABI).
+    X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None; alpha: cuda float32 with 1 or N entries.
+
+    Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
+    handle was uploaded to and the one holding X, b, alpha and Y."""
+    import torch
+    M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
+    if alpha is not None and not (alpha.is_cuda and alpha.dtype == torch.float32 and alpha.is_contiguous()
+                                  and alpha.numel() in (1, N) and alpha.device.index == X.device.index):
+        raise ValueError("alpha must be a contiguous float32 CUDA tensor with 1 or N entries on X's device")
     if alpha is None:
         rc = _load().tstgemm(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
     else:
@@ -232,6 +246,40 @@ def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
     if rc != 0:
         raise TstgemmError(rc, "tstgemm")
     return Y
+
+
+def tstgemm_signed(X, t: Tcsc, b=None, Y=None, stream=None):
+    """Y = X W + b for M <= 8 from the inverted-index form of the uploaded matrix (tstgemm_signed of the C ABI)."""
+    M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
+    rc = _load().tstgemm_signed(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if rc != 0:
+        raise TstgemmError(rc, "tstgemm_signed")
+    return Y
+
+
+def tstgemm_packed(X, t: Tcsc, b=None, Y=None, stream=None):
+    """Y = X W + b for M <= 8 from the value-compression form of the uploaded matrix (tstgemm_packed of the C ABI);
+    X must be finite."""
+    M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
+    rc = _load().tstgemm_packed(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if rc != 0:
+        raise TstgemmError(rc, "tstgemm_packed")
+    return Y
+
+
+def tcsc_signed_arrays(t: Tcsc):
+    """(col_start, index) of the inverted-index encoding: int32 arrays of N + 1 and nnz entries (host)."""
+    col_start = np.empty(t.N + 1, np.int32)
+    index = np.empty(max(t.nnz, 1), np.int32)
+    _check(_load().tcsc_signed_arrays(t.handle, _np_ptr(col_start), _np_ptr(index)), "tcsc_signed_arrays")
+    return col_start, index[:t.nnz]
+
+
+def tcsc_packed_codes(t: Tcsc) -> np.ndarray:
+    """The value-compression encoding: uint8 [N, ceil(K / 5)] (host)."""
+    codes = np.empty((t.N, (t.K + 4) // 5), np.uint8)
+    _check(_load().tcsc_packed_codes(t.handle, _np_ptr(codes)), "tcsc_packed_codes")
+    return codes
 
 
 def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0, slab_tiles: int = 0):

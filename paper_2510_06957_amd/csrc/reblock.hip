@@ -9,7 +9,8 @@
 // (layout: tcsc_layout_t in tstgemm.h).
 //
 // A second small kernel cuts the lists at multiples of 256 rows for the small-tile kernel, which walks the
-// original lists: it only needs to know where each block's slice starts.
+// original lists: it only needs to know where each block's slice starts.  Two more write the matrix in the
+// paper's two other encodings (Sec. 3: inverted index, value compression) for the entry points that read those.
 //
 // Integer work only, run once per matrix at upload time.
 #include "tstgemm_internal.h"
@@ -73,6 +74,63 @@ k_list_cuts(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, co
     cuts[2 * id + 1] = neg;
 }
 
+// Inverted index (Sec. 3 of the paper): one thread per column merges the column's two ascending lists into one,
+// ascending in the row number, a -1 entry of row i stored as ~i.  Column n's merged list starts at
+// col_start_pos[n] + col_start_neg[n].
+__global__ void __launch_bounds__(kThreads)
+k_merge_signed(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, const int32_t *__restrict__ rip,
+               const int32_t *__restrict__ rin, int32_t *__restrict__ merged, int N)
+{
+    const int n = blockIdx.x * kThreads + threadIdx.x;
+    if (n >= N) return;
+    int p = csp[n], q = csn[n];
+    const int p1 = csp[n + 1], q1 = csn[n + 1];
+    int32_t *out = merged + p + q;
+    while (p < p1 && q < q1) {
+        const int rp = rip[p], rq = rin[q];
+        if (rp < rq) { *out++ = rp; ++p; } else { *out++ = ~rq; ++q; }
+    }
+    while (p < p1) *out++ = rip[p++];
+    while (q < q1) *out++ = ~rin[q++];
+}
+
+// Value compression (Sec. 3 of the paper): five consecutive rows of a column as one base-3 number, digit 0 / 1 / 2 for
+// an entry 0 / +1 / -1, first row most significant.  One thread per (chunk of 16 groups, column) reads the 80 rows
+// from the row sets and stores its 16 bytes at once.
+__global__ void __launch_bounds__(kThreads)
+k_pack5(const unsigned long long *__restrict__ masks, uint8_t *__restrict__ packed, int n_pad, int n_kblocks,
+        int n_chunks5)
+{
+    const long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (id >= (long long)n_pad * n_chunks5) return;
+    const int n = (int)(id % n_pad), chunk = (int)(id / n_pad);
+    unsigned long long pos = 0, neg = 0;
+    int have_kb = -1;
+    uint32_t words[kChunk5 / 4];
+#pragma unroll
+    for (int j = 0; j < kChunk5; ++j) {
+        unsigned code = 0;
+#pragma unroll
+        for (int r = 0; r < 5; ++r) {
+            const long long row = ((long long)chunk * kChunk5 + j) * 5 + r;
+            const int kb = (int)(row >> 6);
+            unsigned digit = 0;
+            if (kb < n_kblocks) {
+                if (kb != have_kb) {
+                    pos = masks[2 * ((size_t)kb * n_pad + n)];
+                    neg = masks[2 * ((size_t)kb * n_pad + n) + 1];
+                    have_kb = kb;
+                }
+                digit = (unsigned)((pos >> (row & 63)) & 1) + 2u * (unsigned)((neg >> (row & 63)) & 1);
+            }
+            code = code * 3 + digit;
+        }
+        if (j % 4 == 0) words[j / 4] = code; else words[j / 4] |= code << (8 * (j % 4));
+    }
+    uint4 v = {words[0], words[1], words[2], words[3]};
+    *reinterpret_cast<uint4 *>(packed + (size_t)id * kChunk5) = v;
+}
+
 }  // namespace
 
 hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
@@ -89,6 +147,13 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
     hipLaunchKernelGGL(k_list_cuts, dim3((unsigned)((cut_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
                        d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.list_cuts, l.N, l.n_pad,
                        l.n_cuts);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(k_merge_signed, dim3((unsigned)((l.N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                       d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.signed_index, l.N);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const long long pack_cells = (long long)l.n_pad * l.n_chunks5;
+    hipLaunchKernelGGL(k_pack5, dim3((unsigned)((pack_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                       d.masks, d.packed, l.n_pad, l.n_kblocks, l.n_chunks5);
     return hipGetLastError();
 }
 

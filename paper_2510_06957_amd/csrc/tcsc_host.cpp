@@ -31,6 +31,11 @@ void compute_layout(tcsc *t)
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + tst::kIndexSlack));
     l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
     l.off_list_cuts = place(2 * sizeof(int32_t) * (size_t)(l.n_cuts + 1) * (size_t)l.n_pad);
+    l.off_signed_index = place(sizeof(int32_t) * (size_t)(l.nnz_pos + l.nnz_neg + tst::kIndexSlack));
+    const int groups5 = (t->K + 4) / 5;
+    l.n_chunks5 = (groups5 + tst::kChunk5 - 1) / tst::kChunk5;
+    l.reserved = 0;
+    l.off_packed = place((size_t)l.n_chunks5 * (size_t)l.n_pad * tst::kChunk5);
     l.workspace_bytes = tst::workspace_bytes(l.n_kblocks);
     l.off_workspace = place(l.workspace_bytes);
     l.total_bytes = off;
@@ -168,6 +173,41 @@ int tcsc_arrays(const tcsc_t *t, const int32_t **csp, const int32_t **csn, const
     return TSTGEMM_OK;
 }
 
+int tcsc_signed_arrays(const tcsc_t *t, int32_t *col_start, int32_t *index)
+{
+    if (!t || !col_start || (!index && !(t->row_index_pos.empty() && t->row_index_neg.empty()))) return TSTGEMM_EINVAL;
+    int32_t out = 0;
+    for (int n = 0; n < t->N; ++n) {
+        col_start[n] = out;
+        int32_t p = t->col_start_pos[n], q = t->col_start_neg[n];
+        const int32_t p1 = t->col_start_pos[n + 1], q1 = t->col_start_neg[n + 1];
+        while (p < p1 && q < q1) {
+            if (t->row_index_pos[p] < t->row_index_neg[q]) index[out++] = t->row_index_pos[p++];
+            else index[out++] = ~t->row_index_neg[q++];
+        }
+        while (p < p1) index[out++] = t->row_index_pos[p++];
+        while (q < q1) index[out++] = ~t->row_index_neg[q++];
+    }
+    col_start[t->N] = out;
+    return TSTGEMM_OK;
+}
+
+int tcsc_packed_codes(const tcsc_t *t, uint8_t *codes)
+{
+    if (!t || !codes) return TSTGEMM_EINVAL;
+    static const uint8_t weight[5] = {81, 27, 9, 3, 1};   // value of digit 1 at row j of a group
+    const size_t groups = (size_t)(t->K + 4) / 5;
+    std::memset(codes, 0, groups * (size_t)t->N);
+    for (int n = 0; n < t->N; ++n) {
+        uint8_t *col = codes + (size_t)n * groups;
+        for (int32_t i = t->col_start_pos[n]; i < t->col_start_pos[n + 1]; ++i)
+            col[t->row_index_pos[i] / 5] += weight[t->row_index_pos[i] % 5];
+        for (int32_t i = t->col_start_neg[n]; i < t->col_start_neg[n + 1]; ++i)
+            col[t->row_index_neg[i] / 5] += 2 * weight[t->row_index_neg[i] % 5];
+    }
+    return TSTGEMM_OK;
+}
+
 int tcsc_device_bytes(const tcsc_t *t, size_t *bytes)
 {
     if (!t || !bytes) return TSTGEMM_EINVAL;
@@ -238,6 +278,22 @@ int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *
 {
     if (!alpha || (alpha_count != 1 && alpha_count != N)) return TSTGEMM_EINVAL;
     return run(X, t, b, tst::Activation{alpha, alpha_count == 1 ? 0 : 1}, Y, M, K, N, stream);
+}
+
+int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
+{
+    if (!X || !t || !Y || M < 1 || M > 8 || K != t->K || N != t->N) return TSTGEMM_EINVAL;
+    if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
+    return tst::launch_decode_signed(X, t, b, Y, M, static_cast<hipStream_t>(stream)) == hipSuccess ? TSTGEMM_OK
+                                                                                                  : TSTGEMM_EHIP;
+}
+
+int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
+{
+    if (!X || !t || !Y || M < 1 || M > 8 || K != t->K || N != t->N) return TSTGEMM_EINVAL;
+    if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
+    return tst::launch_packed(X, t, b, Y, M, static_cast<hipStream_t>(stream)) == hipSuccess ? TSTGEMM_OK
+                                                                                           : TSTGEMM_EHIP;
 }
 
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)

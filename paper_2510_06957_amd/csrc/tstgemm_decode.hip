@@ -36,12 +36,14 @@ template <int MM> __device__ __forceinline__ void wave_sum(float (&v)[MM])
 // Rows of X a chunk holds for MM rows of X: all of the LDS budget but one row of zeros.
 template <int MM> constexpr int chunk_rows() { return kDecodeMaxLds / (MM * (int)sizeof(float)) - 1; }
 
-// The part of the ascending list rows[p .. p1) with row numbers below k_hi: gathered and added to (SIGN: subtracted
-// from) acc; p moves to the first entry that was not consumed.  xs_base points k_lo rows in front of the chunk in
-// the LDS, so that xs_base[k * MM + m] is X[m][k] for k in [k_lo, k_hi); row k_zero of that view holds zeros.
-// The sweep is 16-byte aligned, in rounds of 256 entries per wavefront; slots in front of p or behind the last
-// consumed entry gather the row of zeros.  CHUNKED = false: the chunk is all of K, nothing can be late.
-template <int MM, bool SIGN, bool CHUNKED>
+// The part of the ascending list rows[p .. p1) with row numbers below k_hi: gathered and added to (MODE 1: subtracted
+// from) acc; p moves to the first entry that was not consumed.  MODE 2: a merged list of the inverted-index form
+// (Sec. 3), an entry i >= 0 adds row i, an entry ~i < 0 subtracts row i: the sign bit of the entry is flipped into the
+// operand, no branch.  xs_base points k_lo rows in front of the chunk in the LDS, so that xs_base[k * MM + m] is
+// X[m][k] for k in [k_lo, k_hi); row k_zero of that view holds zeros.  The sweep is 16-byte aligned, in rounds of 256
+// entries per wavefront; slots in front of p or behind the last consumed entry gather the row of zeros.
+// CHUNKED = false: the chunk is all of K, nothing can be late.
+template <int MM, int MODE, bool CHUNKED>
 __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__restrict__ rows, int &p, int p1, int k_hi,
                                             int k_zero, const float *xs_base, int lane)
 {
@@ -53,12 +55,17 @@ __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__r
 #pragma unroll
         for (int e = 3; e >= 0; --e) {
             const bool live = i + e >= p && i + e < p1;
-            const bool late = CHUNKED && live && q[e] >= k_hi;
+            const int row = MODE == 2 ? (q[e] ^ (q[e] >> 31)) : q[e];
+            const unsigned flip = MODE == 2 ? ((unsigned)q[e] & 0x80000000u) : 0u;
+            const bool late = CHUNKED && live && row >= k_hi;
             if (late) first_late = e;
-            const int k = (live && !late) ? q[e] : k_zero;
+            const int k = (live && !late) ? row : k_zero;
 #pragma unroll
             for (int m = 0; m < MM; ++m) {
-                if (SIGN) acc[m] -= xs_base[(size_t)k * MM + m]; else acc[m] += xs_base[(size_t)k * MM + m];
+                const float x = xs_base[(size_t)k * MM + m];
+                if (MODE == 1) acc[m] -= x;
+                else if (MODE == 2) acc[m] += __uint_as_float(__float_as_uint(x) ^ flip);
+                else acc[m] += x;
             }
         }
         const unsigned long long late_lanes = CHUNKED ? __ballot(first_late < 4) : 0ull;
@@ -73,7 +80,8 @@ __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__r
     p = p1;
 }
 
-template <int MM, bool CHUNKED>
+// SIGNED: rip is the merged list of the inverted-index form (column n at col_start_pos[n] + col_start_neg[n]), rin unused.
+template <int MM, bool CHUNKED, bool SIGNED>
 __global__ void __launch_bounds__(kDecodeThreads)
 k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int32_t *__restrict__ csn,
          const int32_t *__restrict__ rip, const int32_t *__restrict__ rin, const float *__restrict__ b,
@@ -104,6 +112,7 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
         const bool have = n < N;
         int pp = have ? csp[n] : 0, pp1 = have ? csp[n + 1] : 0;
         int pn = have ? csn[n] : 0, pn1 = have ? csn[n + 1] : 0;
+        if (SIGNED) { pp += pn; pp1 += pn1; pn = pn1 = 0; }
         float acc[MM];
 #pragma unroll
         for (int m = 0; m < MM; ++m) acc[m] = 0.f;
@@ -116,8 +125,12 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
             const int k_lo = c * kc;
             const int k_hi = (c + 1 == n_chunks) ? 0x7fffffff : k_lo + kc;
             const float *xs_base = xs - (size_t)k_lo * MM;
-            run_sublist<MM, false, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
-            run_sublist<MM, true, CHUNKED>(acc, rin, pn, pn1, k_hi, k_lo + kc, xs_base, lane);
+            if (SIGNED) {
+                run_sublist<MM, 2, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
+            } else {
+                run_sublist<MM, 0, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
+                run_sublist<MM, 1, CHUNKED>(acc, rin, pn, pn1, k_hi, k_lo + kc, xs_base, lane);
+            }
         }
         if (!have) continue;
         wave_sum<MM>(acc);
@@ -128,20 +141,17 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
     }
 }
 
-template <int MM>
-hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
+template <int MM, bool CHUNKED, bool SIGNED>
+hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int kc, size_t lds,
+                         hipStream_t stream)
 {
     const DeviceTcsc d = device_view(t);
-    const int kc = t->K < chunk_rows<MM>() ? t->K : chunk_rows<MM>();
-    const size_t lds = (size_t)(kc + 1) * MM * sizeof(float);
-    const bool chunked = t->K > kc;
-    const void *kernel = chunked ? reinterpret_cast<const void *>(&k_decode<MM, true>)
-                                 : reinterpret_cast<const void *>(&k_decode<MM, false>);
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[chunked]) {
-        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM, CHUNKED, SIGNED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
         if (e != hipSuccess) return e;
-        attr_set[chunked] = true;
+        attr_set = true;
     }
     const int per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
     int grid = compute_units() * per_cu;
@@ -149,17 +159,38 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     if (grid > need) grid = need;
     hipError_t e;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    if (chunked)
-        hipLaunchKernelGGL((k_decode<MM, true>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
-                           d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K,
-                           t->N, kc);
-    else
-        hipLaunchKernelGGL((k_decode<MM, false>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
-                           d.col_start_neg, d.row_index_pos, d.row_index_neg, b, act.alpha, act.alpha_stride, Y, t->K,
-                           t->N, kc);
+    hipLaunchKernelGGL((k_decode<MM, CHUNKED, SIGNED>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
+                       d.col_start_neg, SIGNED ? d.signed_index : d.row_index_pos, d.row_index_neg, b, act.alpha,
+                       act.alpha_stride, Y, t->K, t->N, kc);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     return e;
+}
+
+template <int MM, bool SIGNED>
+hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
+{
+    const int kc = t->K < chunk_rows<MM>() ? t->K : chunk_rows<MM>();
+    const size_t lds = (size_t)(kc + 1) * MM * sizeof(float);
+    return t->K > kc ? launch_kernel<MM, true, SIGNED>(X, t, b, act, Y, kc, lds, stream)
+                     : launch_kernel<MM, false, SIGNED>(X, t, b, act, Y, kc, lds, stream);
+}
+
+template <bool SIGNED>
+hipError_t launch_m(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
+                    hipStream_t stream)
+{
+    switch (M) {
+    case 1: return launch<1, SIGNED>(X, t, b, act, Y, stream);
+    case 2: return launch<2, SIGNED>(X, t, b, act, Y, stream);
+    case 3: return launch<3, SIGNED>(X, t, b, act, Y, stream);
+    case 4: return launch<4, SIGNED>(X, t, b, act, Y, stream);
+    case 5: return launch<5, SIGNED>(X, t, b, act, Y, stream);
+    case 6: return launch<6, SIGNED>(X, t, b, act, Y, stream);
+    case 7: return launch<7, SIGNED>(X, t, b, act, Y, stream);
+    case 8: return launch<8, SIGNED>(X, t, b, act, Y, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -169,17 +200,12 @@ bool decode_supported(int M, int K) { (void)K; return M <= 8; }
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream)
 {
-    switch (M) {
-    case 1: return launch<1>(X, t, b, act, Y, stream);
-    case 2: return launch<2>(X, t, b, act, Y, stream);
-    case 3: return launch<3>(X, t, b, act, Y, stream);
-    case 4: return launch<4>(X, t, b, act, Y, stream);
-    case 5: return launch<5>(X, t, b, act, Y, stream);
-    case 6: return launch<6>(X, t, b, act, Y, stream);
-    case 7: return launch<7>(X, t, b, act, Y, stream);
-    case 8: return launch<8>(X, t, b, act, Y, stream);
-    default: return hipErrorInvalidValue;
-    }
+    return launch_m<false>(X, t, b, act, Y, M, stream);
+}
+
+hipError_t launch_decode_signed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+{
+    return launch_m<true>(X, t, b, Activation{nullptr, 0}, Y, M, stream);
 }
 
 }  // namespace tst

@@ -13,7 +13,8 @@ namespace tst {
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
 constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
-constexpr int kIndexSlack = 32;   // entries behind each index array that may be read (never used)
+constexpr int kIndexSlack = 32;
+constexpr int kChunk5 = 16;   // groups of five rows (bytes) per column and chunk of the value-compression form   // entries behind each index array that may be read (never used)
 constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: [k_slices][padded rows][n_pad] fp32
 constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
 
@@ -49,6 +50,8 @@ struct DeviceTcsc {
     const int32_t *col_start_pos, *col_start_neg, *row_index_pos, *row_index_neg;
     unsigned long long *masks;   // [n_kblocks][n_pad][2]
     int32_t *list_cuts;          // [n_cuts + 1][n_pad][2]
+    int32_t *signed_index;       // merged lists, -1 entries as ~row
+    uint8_t *packed;             // [n_chunks5][n_pad][16] base-3 codes
     float *partials;     // split-K partial sums
     float *xt;           // xt[tile][k][row]: row tiles of (a slab of) X, transposed, zero padded
     size_t xt_capacity;  // bytes
@@ -64,6 +67,8 @@ inline DeviceTcsc device_view(const tcsc *t)
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_neg),
                       reinterpret_cast<unsigned long long *>(d + l.off_masks),
                       reinterpret_cast<int32_t *>(d + l.off_list_cuts),
+                      reinterpret_cast<int32_t *>(d + l.off_signed_index),
+                      reinterpret_cast<uint8_t *>(d + l.off_packed),
                       reinterpret_cast<float *>(d + l.off_workspace),
                       reinterpret_cast<float *>(d + l.off_workspace + kPartialBytes),
                       xt_bytes(l.n_kblocks)};
@@ -97,5 +102,9 @@ extern hipEvent_t g_event_before, g_event_after;       // recorded around the ma
 bool decode_supported(int M, int K);
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream);
+// the same kernel on the merged signed lists (inverted index)
+hipError_t launch_decode_signed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);
+// tstgemm_packed.hip -- M <= 8 from the base-3 codes (value compression)
+hipError_t launch_packed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream);
 
 }  // namespace tst

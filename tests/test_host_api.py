@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(str(tg.library_path()))
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
-            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_set_tuning", "tstgemm_profile_events",
-            "tcsc_destroy",
+            "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tcsc_signed_arrays", "tcsc_packed_codes",
+            "tstgemm_signed", "tstgemm_packed", "tstgemm_set_tuning", "tstgemm_profile_events", "tcsc_destroy",
             "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
@@ -102,6 +102,13 @@ def test_not_uploaded_and_dimension_errors():
     assert lib.tstgemm(fake, t.handle, None, fake, 2, K + 1, N, None) == -1
     assert lib.tstgemm(fake, t.handle, None, fake, 0, K, N, None) == -1
     assert lib.tstgemm(None, t.handle, None, fake, 2, K, N, None) == -1
+    # the two small-M variants: the same checks, and M <= 8 only
+    for fn in (lib.tstgemm_signed, lib.tstgemm_packed):
+        fn.argtypes = lib.tstgemm.argtypes
+        assert fn(fake, t.handle, None, fake, 2, K, N, None) == -3
+        assert fn(fake, t.handle, None, fake, 9, K, N, None) == -1
+        assert fn(fake, t.handle, None, fake, 2, K, N + 1, None) == -1
+        assert fn(None, t.handle, None, fake, 2, K, N, None) == -1
     for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(tg.tcsc_strerror(code), str) and tg.tcsc_strerror(code)
 
@@ -113,11 +120,15 @@ def test_layout_bookkeeping():
     assert (lay.K, lay.N, lay.k_block) == (513, 65, 64)
     assert lay.n_pad % 64 == 0 and lay.n_pad >= 65 and lay.n_kblocks == -(-513 // 64)
     assert (lay.nnz_pos, lay.nnz_neg) == (int((W == 1).sum()), int((W == -1).sum()))
+    assert lay.n_cuts == 3 and lay.n_chunks5 == 7          # 513 rows: 3 cuts of 256, 103 groups of five in 7 chunks of 16
     offs = [lay.off_col_start_pos, lay.off_col_start_neg, lay.off_row_index_pos, lay.off_row_index_neg,
-            lay.off_masks, lay.off_workspace, lay.total_bytes]
+            lay.off_masks, lay.off_list_cuts, lay.off_signed_index, lay.off_packed, lay.off_workspace, lay.total_bytes]
     assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
     assert lay.total_bytes == tg.tcsc_device_bytes(t)
-    assert lay.off_workspace - lay.off_masks >= 16 * lay.n_kblocks * lay.n_pad
+    assert lay.off_list_cuts - lay.off_masks >= 16 * lay.n_kblocks * lay.n_pad
+    assert lay.off_signed_index - lay.off_list_cuts >= 8 * (lay.n_cuts + 1) * lay.n_pad
+    assert lay.off_packed - lay.off_signed_index >= 4 * (lay.nnz_pos + lay.nnz_neg)
+    assert lay.off_workspace - lay.off_packed >= 16 * lay.n_chunks5 * lay.n_pad
     assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
 
 
@@ -131,3 +142,16 @@ def test_tuning_rejects_bad_values():
     one = ctypes.c_void_p(1)
     assert lib.tstgemm_profile_events(one, None) == -1
     assert lib.tstgemm_profile_events(None, None) == 0
+
+
+@pytest.mark.parametrize("K,N,density", [(1, 1, 1.0), (37, 5, 0.5), (513, 65, 0.5), (64, 9, 1.0), (130, 70, 0.0),
+                                         (1000, 33, 0.0625)])
+def test_other_encodings_match_the_oracle(K, N, density):
+    """The host exporters of the inverted-index and value-compression encodings (Sec. 3) against the oracle's."""
+    W, _, _ = si.make_inputs(1, K, N, density, "uniform", seed=150 + K + N)
+    t = tg.tcsc_build(W)
+    cs, idx = tg.tcsc_signed_arrays(t)
+    ocs, oidx = oracle.signed_build(oracle.tcsc_build(W))
+    assert np.array_equal(cs, ocs) and np.array_equal(idx, oidx)
+    assert np.array_equal(tg.tcsc_packed_codes(t), oracle.pack5(W))
+    assert np.array_equal(oracle.unpack5(tg.tcsc_packed_codes(t), K), W)
