@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse ternary GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--variant tcsc|signed|packed]
 
 One step = one tstgemm() call (the whole hot path: X packing / tile staging, gather-add, K-block carry,
 split-K reduction, bias epilogue) on one batch of synthetic input that is already resident in HBM.  The
@@ -27,6 +27,7 @@ import numpy as np
 PEAK_LDS_GATHER_TFLOPS = 256 * 256 * 2.4e9 / 4 / 1e12
 PEAK_ALU_ADD_TFLOPS = 157.3 / 2
 PEAK_HBM_GBS = 8000.0
+PEAK_ALU_INSTR_T = 256 * 64 * 2.4e9 / 1e12     # vector lane-instructions per second (an FMA counts once)
 
 # HBM bytes of one launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
 # (profiles/tstgemm_C2_hbm_traffic.md), each counter scaled by what it reads for a copy kernel of known size in the
@@ -34,20 +35,29 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {"C2": (12448 + 32768) * 1024}
 
 
-def cpu_baseline(W, X, b, nnz, budget_s=10.0):
+def cpu_baseline(W, X, b, nnz, variant="tcsc", budget_s=10.0):
     """The oracle as it stands, on the host cores, on the same workload; repeated for about budget_s."""
     import oracle
     t = oracle.tcsc_build(W)
-    M = X.shape[0]
+    M, K = X.shape
     rows = None
     if M * nnz > 4e10:   # keep the sample to seconds: a slice of rows (the cost per row does not depend on M)
         rows = np.arange(0, M, M // 64, dtype=np.int32)[:64]
+    if variant == "signed":
+        enc = oracle.signed_build(t)
+    elif variant == "packed":
+        enc = oracle.pack5(W)
     times = []
-    used = 0
+    used = os.cpu_count() or 1   # the variant routines do not report their thread count: OpenMP's default, all cores
     t_start = time.perf_counter()
     while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 200):
         t0 = time.perf_counter()
-        _, _, used = oracle.tstgemm(X, t, b) if rows is None else oracle.tstgemm(X, t, b, rows=rows)
+        if variant == "signed":
+            oracle.tstgemm_signed(X, enc[0], enc[1], b, K)
+        elif variant == "packed":
+            oracle.tstgemm_packed(X, enc, b, K)
+        else:
+            _, _, used = oracle.tstgemm(X, t, b) if rows is None else oracle.tstgemm(X, t, b, rows=rows)
         times.append(time.perf_counter() - t0)
     mean = float(np.mean(times))
     m_used = M if rows is None else len(rows)
@@ -63,6 +73,9 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--variant", default="tcsc", choices=["tcsc", "signed", "packed"],
+                    help="tcsc: tstgemm(); signed / packed: the M <= 8 entry points on the paper's inverted-index / "
+                         "value-compression encodings (Sec. 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain 256 MiB copy kernel a few times (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: "
@@ -82,6 +95,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     wl = si.workload(args.workload)
+    if args.variant != "tcsc" and wl.M > 8:
+        print("bench.py: the signed and packed variants are small-M paths (M <= 8)", file=sys.stderr)
+        sys.exit(2)
+    gemm = {"tcsc": tg.tstgemm, "signed": tg.tstgemm_signed, "packed": tg.tstgemm_packed}[args.variant]
     W, X, b = si.make_workload(wl.name)
     t0 = time.perf_counter()
     t = tg.tcsc_build(W)
@@ -113,14 +130,14 @@ def main():
         del src, dst
 
     for _ in range(warmup):
-        tg.tstgemm(Xd, t, bd, Yd, stream)
+        gemm(Xd, t, bd, Yd, stream)
     torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(steps):
-        tg.tstgemm(Xd, t, bd, Yd, stream)
+        gemm(Xd, t, bd, Yd, stream)
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -137,7 +154,7 @@ def main():
     torch.cuda.synchronize()
     for a, c in pairs:
         tg.tstgemm_profile_events(a, c)
-        tg.tstgemm(Xd, t, bd, Yd, stream)
+        gemm(Xd, t, bd, Yd, stream)
     tg.tstgemm_profile_events(None, None)
     torch.cuda.synchronize()
     kernel_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
@@ -145,8 +162,17 @@ def main():
     decode = wl.M <= 8          # the library's rules for its decode kernel ...
     small = 8 < wl.M <= 64      # ... and its small-tile kernel
     traffic = MEASURED_TRAFFIC.get(wl.name)
-    if decode:
-        # small-M path streams the four TCSC arrays once: index-bandwidth bound
+    if args.variant == "packed":
+        # dense decode: every entry of the padded W costs one conversion and M multiply-adds on the vector ALUs
+        # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s); the codes are 1.6 bits per entry
+        entries = lay.n_chunks5 * 80 * lay.n_pad
+        alg_bytes = lay.n_chunks5 * lay.n_pad * 16 + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
+        roof = {"bound": "alu", "achieved": entries * (wl.M + 1) / (kernel_ms * 1e-3) / 1e12, "peak": PEAK_ALU_INSTR_T,
+                "unit": "T lane-instructions/s", "traffic": traffic,
+                "note": "per entry of W (zeros included): 1 byte-to-float conversion + M fused multiply-adds; "
+                        "peak = 256 CUs x 64 lanes x 2.4 GHz (one vector instruction per SIMD and 4 clocks)"}
+    elif decode:
+        # small-M path streams the index arrays once (TCSC: four arrays; signed: one pointer array less): index-bandwidth bound
         alg_bytes = 4 * nnz + 8 * (wl.N + 1) + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
         roof = {"bound": "hbm", "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "traffic": traffic}
@@ -161,14 +187,14 @@ def main():
                         "2.4 GHz; the fp32 add rate of the vector ALUs (alu_add_peak) is twice that",
                 "alu_add_peak": PEAK_ALU_ADD_TFLOPS}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = "k_decode" if decode else "k_small" if small else "k_large"
+    roof["kernel"] = ("k_packed" if args.variant == "packed" else "k_decode (signed lists)" if args.variant == "signed"
+                      else "k_decode" if decode else "k_small" if small else "k_large")
     roof["kernel_ms"] = kernel_ms
     roof["algorithmic_adds_per_launch"] = adds
     roof["algorithmic_bytes_per_launch"] = alg_bytes
     # the same accounting for the whole call (packing pre-pass + main kernel + split-K reduction)
     roof["call_ms"] = call_ms
-    roof["call_frac"] = (alg_bytes / (call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if decode
-                         else adds / (call_ms * 1e-3) / 1e12 / PEAK_LDS_GATHER_TFLOPS)
+    roof["call_frac"] = roof["frac"] * kernel_ms / call_ms   # the same work over the time of the whole call
     if not decode:
         roof["alu_frac"] = roof["achieved"] / PEAK_ALU_ADD_TFLOPS
 
@@ -179,13 +205,13 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: M={wl.M} K={wl.K} N={wl.N} density={wl.density} X,b~{wl.dist} "
-                               f"seed={wl.seed}", "nnz": nnz,
+                               f"seed={wl.seed}", "nnz": nnz, "variant": args.variant,
                    "index_type": "int32 TCSC in; on device the TCSC arrays (M <= 64) or 64-bit row sets per K-block",
                    "tcsc_build_ms_host": build_ms, "upload_and_reblock_ms": upload_ms},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(W, X, b, nnz)
+        out["cpu_baseline"] = cpu_baseline(W, X, b, nnz, args.variant)
     print(json.dumps(out))
 
 

@@ -18,7 +18,7 @@
  *     then the bias.  Additions and subtractions only, no multiplication.
  *
  * Readings where the paper is silent: indices are 0-based int32, ascending inside a
- * column ("sorted within individual columns", Sec. 3 Blocking); X and Y are row-major;
+ * column (Sec. 3, Blocking, relies on that order); X and Y are row-major;
  * the accumulator starts at zero and the bias is one final addition (the cost model
  * M N (1 + s K) of Sec. 2 counts exactly one add per output for it).
  *
