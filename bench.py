@@ -157,7 +157,16 @@ def main():
         gemm(Xd, t, bd, Yd, stream)
     tg.tstgemm_profile_events(None, None)
     torch.cuda.synchronize()
-    kernel_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
+    kernel_raw_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
+    # What an event pair reads with nothing between its two records, on the same busy stream: the cost of the
+    # second record itself, which the pair around the kernel contains as well.
+    for a, c in pairs:
+        gemm(Xd, t, bd, Yd, stream)
+        a.record(stream)
+        c.record(stream)
+    torch.cuda.synchronize()
+    pair_ms = float(np.mean([a.elapsed_time(c) for a, c in pairs]))
+    kernel_ms = kernel_raw_ms - pair_ms
 
     decode = wl.M <= 8          # the library's rules for its decode kernel ...
     small = 8 < wl.M <= 64      # ... and its small-tile kernel
@@ -190,6 +199,8 @@ def main():
     roof["kernel"] = ("k_packed" if args.variant == "packed" else "k_decode (signed lists)" if args.variant == "signed"
                       else "k_decode" if decode else "k_small" if small else "k_large")
     roof["kernel_ms"] = kernel_ms
+    roof["kernel_ms_event_pair"] = kernel_raw_ms     # as read from the event pair ...
+    roof["empty_event_pair_ms"] = pair_ms            # ... minus what an empty pair reads = kernel_ms
     roof["algorithmic_adds_per_launch"] = adds
     roof["algorithmic_bytes_per_launch"] = alg_bytes
     # the same accounting for the whole call (packing pre-pass + main kernel + split-K reduction)

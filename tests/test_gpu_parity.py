@@ -110,6 +110,21 @@ def test_benchmark_configs_full(name, dist):
         assert_close(Y, Yd, A, name)
 
 
+@pytest.mark.parametrize("name", ["M64-K16384-N4096-d0.5", "M64-K4096-N4096-d0.0625", "M32-K16384-N1024-d0.25",
+                                  "M8-K8192-N4096-d0.5", "M1024-K4096-N1024-d0.25"])
+def test_paper_sweep_shapes_full(name):
+    """Every element of the largest shapes of the paper's own sweeps (Sec. 4), one per kernel and tile height, in the
+    launch configuration bench.py times; an integer-valued run bit for bit."""
+    W, X, b = si.make_workload(name)
+    ot = oracle.tcsc_build(W)
+    Y, h = gpu_tstgemm(W, X, b)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    assert_close(Y, Yd, A, name)
+    Xi = si.draw_dense(np.random.Generator(np.random.PCG64(6)), X.shape, "int8")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+
+
 @pytest.mark.parametrize("name", ["C5a", "C5c"])
 def test_prefill_config_sampled_rows(name):
     """M=4096, K=N=8192: all of Y is computed on the GPU; the oracle checks 24 whole rows (one per M-tile and a few
