@@ -74,24 +74,27 @@ k_list_cuts(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, co
     cuts[2 * id + 1] = neg;
 }
 
-// Inverted index (Sec. 3 of the paper): one thread per column merges the column's two ascending lists into one,
-// ascending in the row number, a -1 entry of row i stored as ~i.  Column n's merged list starts at
-// col_start_pos[n] + col_start_neg[n].
+// Inverted index (Sec. 3 of the paper): the two ascending lists of a column merged into one, ascending in the row
+// number, a -1 entry of row i stored as ~i.  Column n's merged list starts at col_start_pos[n] + col_start_neg[n].
+// One thread per entry: its place in the merged list is its place in its own list plus the number of entries of the
+// other list with a smaller row (no row is in both).  SIGN: the entries of the -1 list.
+template <bool SIGN>
 __global__ void __launch_bounds__(kThreads)
-k_merge_signed(const int32_t *__restrict__ csp, const int32_t *__restrict__ csn, const int32_t *__restrict__ rip,
-               const int32_t *__restrict__ rin, int32_t *__restrict__ merged, int N)
+k_merge_signed(const int32_t *__restrict__ cs_own, const int32_t *__restrict__ cs_other,
+               const int32_t *__restrict__ ri_own, const int32_t *__restrict__ ri_other, int32_t *__restrict__ merged,
+               int N, int nnz_own)
 {
-    const int n = blockIdx.x * kThreads + threadIdx.x;
-    if (n >= N) return;
-    int p = csp[n], q = csn[n];
-    const int p1 = csp[n + 1], q1 = csn[n + 1];
-    int32_t *out = merged + p + q;
-    while (p < p1 && q < q1) {
-        const int rp = rip[p], rq = rin[q];
-        if (rp < rq) { *out++ = rp; ++p; } else { *out++ = ~rq; ++q; }
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nnz_own) return;
+    // the column of entry i: the last n with cs_own[n] <= i
+    int lo = 0, hi = N;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cs_own[mid] <= i) lo = mid; else hi = mid;
     }
-    while (p < p1) *out++ = rip[p++];
-    while (q < q1) *out++ = ~rin[q++];
+    const int n = lo, row = ri_own[i];
+    const int smaller = lower_bound_dev(ri_other, cs_other[n], cs_other[n + 1], row) - cs_other[n];
+    merged[cs_own[n] + cs_other[n] + (i - cs_own[n]) + smaller] = SIGN ? ~row : row;
 }
 
 // Value compression (Sec. 3 of the paper): five consecutive rows of a column as one base-3 number, digit 0 / 1 / 2 for
@@ -148,8 +151,14 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
                        d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.list_cuts, l.N, l.n_pad,
                        l.n_cuts);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(k_merge_signed, dim3((unsigned)((l.N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
-                       d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.signed_index, l.N);
+    if (l.nnz_pos > 0)
+        hipLaunchKernelGGL(k_merge_signed<false>, dim3((unsigned)((l.nnz_pos + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                           stream, d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.signed_index, l.N,
+                           (int)l.nnz_pos);
+    if (l.nnz_neg > 0)
+        hipLaunchKernelGGL(k_merge_signed<true>, dim3((unsigned)((l.nnz_neg + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                           stream, d.col_start_neg, d.col_start_pos, d.row_index_neg, d.row_index_pos, d.signed_index, l.N,
+                           (int)l.nnz_neg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const long long pack_cells = (long long)l.n_pad * l.n_chunks5;
     hipLaunchKernelGGL(k_pack5, dim3((unsigned)((pack_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,

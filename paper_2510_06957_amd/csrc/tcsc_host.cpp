@@ -1,5 +1,5 @@
-// Host side of libtstgemm: handle, TCSC construction and validation (Sec. 2 of the paper),
-// device-buffer layout, upload and the tstgemm() dispatch.
+// Host side of libtstgemm: handle, TCSC construction and validation (Sec. 2 of the paper), the matrix in the paper's
+// two other encodings (Sec. 3), device-buffer layout, upload and the dispatch of the tstgemm*() entry points.
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -258,9 +258,9 @@ int run(const float *X, const tcsc_t *t, const float *b, const tst::Activation &
     if (K != t->K || N != t->N) return TSTGEMM_EINVAL;
     if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = tst::decode_supported(M, K) ? tst::launch_decode(X, t, b, act, Y, M, s)
-                   : M <= 64                   ? tst::launch_small(X, t, b, act, Y, M, s)
-                                               : tst::launch_large(X, t, b, act, Y, M, s);
+    hipError_t e = tst::decode_supported(M) ? tst::launch_decode(X, t, b, act, Y, M, s)
+                   : M <= 64                ? tst::launch_small(X, t, b, act, Y, M, s)
+                                            : tst::launch_large(X, t, b, act, Y, M, s);
     return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
 }
 

@@ -4,7 +4,8 @@
 // operational-intensity argument, Sec. 4), so the kernel is shaped around streaming the TCSC
 // index arrays (Sec. 2) from HBM exactly once, fully coalesced, in their original form:
 //   * X (M x K fp32) is kept in the LDS, transposed to xs[k][m], so one gathered index yields
-//     the M operands of all rows at once.  If all of X does not fit, K is cut into chunks of
+//     the M operands of all rows at once (for M > 4 in two planes of at most four rows of X each: a gather
+//     is then a 16-byte read per plane that can start at any of the 16 bank groups, not only at every other).  If all of X does not fit, K is cut into chunks of
 //     as many rows as fit (the paper's K-blocking, Sec. 3, with the LDS in the place of the L1
 //     cache) and the chunks are taken one after the other; the lists are ascending, so the
 //     part of a list that falls into a chunk is contiguous and a cursor per list is enough;
@@ -13,6 +14,8 @@
 //     at the end), reading 4 consecutive indices per lane with a 16-byte load;
 //   * the M per-lane partial sums are folded across the wavefront by a halving exchange, the
 //     bias is added once, last (then the optional PReLU), and one lane per row stores the result.
+// The same kernel also runs on the paper's inverted-index form (Sec. 3): one merged list per column
+// whose entries carry their sign (i for +1, ~i for -1); the sign bit is flipped into the operand.
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -33,19 +36,27 @@ template <int MM> __device__ __forceinline__ void wave_sum(float (&v)[MM])
     }
 }
 
+// xs: plane p holds rows 4p .. 4p+3 of X (the last plane the rest) as plane[k][width]; every plane has kc + 1 rows, the
+// last one zero.  Offset (in floats) of element (k, m) for a view whose row 0 is row k_lo of X.
+template <int MM> __device__ __forceinline__ int xs_at(int k, int m, int kc1)
+{
+    const int p = m >> 2, width = (MM - 4 * p) < 4 ? (MM - 4 * p) : 4;
+    return 4 * p * kc1 + k * width + (m & 3);
+}
+
 // Rows of X a chunk holds for MM rows of X: all of the LDS budget but one row of zeros.
 template <int MM> constexpr int chunk_rows() { return kDecodeMaxLds / (MM * (int)sizeof(float)) - 1; }
 
 // The part of the ascending list rows[p .. p1) with row numbers below k_hi: gathered and added to (MODE 1: subtracted
 // from) acc; p moves to the first entry that was not consumed.  MODE 2: a merged list of the inverted-index form
 // (Sec. 3), an entry i >= 0 adds row i, an entry ~i < 0 subtracts row i: the sign bit of the entry is flipped into the
-// operand, no branch.  xs_base points k_lo rows in front of the chunk in the LDS, so that xs_base[k * MM + m] is
-// X[m][k] for k in [k_lo, k_hi); row k_zero of that view holds zeros.  The sweep is 16-byte aligned, in rounds of 256
+// operand, no branch.  k_lo is the first row of X in the LDS: xs[xs_at(k - k_lo, m)] is X[m][k] for k in [k_lo, k_hi);
+// row k_zero holds zeros.  The sweep is 16-byte aligned, in rounds of 256
 // entries per wavefront; slots in front of p or behind the last consumed entry gather the row of zeros.
 // CHUNKED = false: the chunk is all of K, nothing can be late.
 template <int MM, int MODE, bool CHUNKED>
 __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__restrict__ rows, int &p, int p1, int k_hi,
-                                            int k_zero, const float *xs_base, int lane)
+                                            int k_zero, const float *xs, int k_lo, int kc1, int lane)
 {
     while (p < p1) {
         const int i = (p & ~3) + lane * 4;
@@ -62,7 +73,7 @@ __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__r
             const int k = (live && !late) ? row : k_zero;
 #pragma unroll
             for (int m = 0; m < MM; ++m) {
-                const float x = xs_base[(size_t)k * MM + m];
+                const float x = xs[xs_at<MM>(k - k_lo, m, kc1)];
                 if (MODE == 1) acc[m] -= x;
                 else if (MODE == 2) acc[m] += __uint_as_float(__float_as_uint(x) ^ flip);
                 else acc[m] += x;
@@ -87,7 +98,8 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
          const int32_t *__restrict__ rip, const int32_t *__restrict__ rin, const float *__restrict__ b,
          const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N, int kc)
 {
-    extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc + 1][MM], row kc is all zero
+    extern __shared__ __attribute__((aligned(16))) float xs[];   // planes of [kc + 1][<= 4], row kc is all zero
+    const int kc1 = kc + 1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves_total = gridDim.x * kDecodeWaves;
@@ -98,10 +110,10 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
         const int k_lo = c * kc, len = min(kc, K - k_lo);
         for (int k = threadIdx.x; k < len; k += kDecodeThreads) {
 #pragma unroll
-            for (int m = 0; m < MM; ++m) xs[k * MM + m] = X[(size_t)m * K + k_lo + k];
+            for (int m = 0; m < MM; ++m) xs[xs_at<MM>(k, m, kc1)] = X[(size_t)m * K + k_lo + k];
         }
     };
-    if (threadIdx.x < MM) xs[kc * MM + threadIdx.x] = 0.f;
+    if (threadIdx.x < MM) xs[xs_at<MM>(kc, threadIdx.x, kc1)] = 0.f;
     if (!CHUNKED) load_chunk(0);   // all of X fits: loaded once, for all columns of this workgroup
     __syncthreads();
 
@@ -124,12 +136,11 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
             }
             const int k_lo = c * kc;
             const int k_hi = (c + 1 == n_chunks) ? 0x7fffffff : k_lo + kc;
-            const float *xs_base = xs - (size_t)k_lo * MM;
             if (SIGNED) {
-                run_sublist<MM, 2, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
+                run_sublist<MM, 2, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs, k_lo, kc1, lane);
             } else {
-                run_sublist<MM, 0, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs_base, lane);
-                run_sublist<MM, 1, CHUNKED>(acc, rin, pn, pn1, k_hi, k_lo + kc, xs_base, lane);
+                run_sublist<MM, 0, CHUNKED>(acc, rip, pp, pp1, k_hi, k_lo + kc, xs, k_lo, kc1, lane);
+                run_sublist<MM, 1, CHUNKED>(acc, rin, pn, pn1, k_hi, k_lo + kc, xs, k_lo, kc1, lane);
             }
         }
         if (!have) continue;
@@ -195,7 +206,7 @@ hipError_t launch_m(const float *X, const tcsc *t, const float *b, const Activat
 
 }  // namespace
 
-bool decode_supported(int M, int K) { (void)K; return M <= 8; }
+bool decode_supported(int M) { return M <= 8; }
 
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream)

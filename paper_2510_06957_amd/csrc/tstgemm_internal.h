@@ -13,9 +13,9 @@ namespace tst {
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
 constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
-constexpr int kIndexSlack = 32;
-constexpr int kChunk5 = 16;   // groups of five rows (bytes) per column and chunk of the value-compression form   // entries behind each index array that may be read (never used)
-constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: [k_slices][padded rows][n_pad] fp32
+constexpr int kIndexSlack = 32;   // entries behind each index array that may be read (never used)
+constexpr int kChunk5 = 16;       // groups of five rows (bytes) per column and chunk of the value-compression form
+constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: workgroup tiles [tile][slice][column][row] fp32
 constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
 
 // The copy holds whole row tiles of X over all (padded) K: at least one tile of 256 rows must fit.
@@ -79,7 +79,7 @@ struct Activation {
     const float *alpha;
     int alpha_stride;
 };
-// reblock.hip -- GPU pass: TCSC arrays (already on the device) -> per-K-block row sets.
+// reblock.hip -- GPU pass: TCSC arrays (already on the device) -> row sets, list cuts, signed lists, base-3 codes.
 hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
 // tstgemm_side.hip -- X packing pre-pass and split-K reduction, shared by the tiled paths.
 constexpr int kMaxKSlices = 8;
@@ -90,7 +90,7 @@ hipError_t launch_pack(const float *X, float *xt, int rows, int K, int k_pad, in
 // Y = sum of the k_slices partial tiles ([tile][slice][C columns][TM rows], C = 16, 32 or 64) in slice order + b, then act.
 hipError_t launch_reduce(int C, const float *partials, const float *b, const Activation &act, float *Y, int M, int N,
                          int m_tiles, int n_colgroups, int k_slices, int TM, hipStream_t stream);
-// tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (64-row tiles).
+// tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (one tile of 64 or 32 rows).
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream);
 // tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 64.
@@ -98,8 +98,8 @@ hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Act
                         hipStream_t stream);
 extern int g_cols_per_wave, g_k_slices, g_slab_tiles;   // tuning overrides, 0 = built-in choice
 extern hipEvent_t g_event_before, g_event_after;       // recorded around the main kernel of a call when set
-// tstgemm_decode.hip -- small-M kernel (M <= 8, whole X resident in the LDS).
-bool decode_supported(int M, int K);
+// tstgemm_decode.hip -- small-M kernel (M <= 8; X in the LDS, in chunks of K if need be).
+bool decode_supported(int M);
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream);
 // the same kernel on the merged signed lists (inverted index)
