@@ -72,7 +72,7 @@ __device__ __forceinline__ void run_piece(float (&acc)[MM], const uint4v &codes,
 // The last piece of a column when K is not a multiple of 80: the same, entry by entry, rows >= K left out (their
 // codes' digits are 0 and their X entries do not exist).  Runs at most once per wavefront.
 template <int MM>
-__device__ __noinline__ void run_last_piece(float (&acc)[MM], const uint4v &codes, const uint2v *lut, const_f32_ptr X, int K,
+__device__ __forceinline__ void run_last_piece(float (&acc)[MM], const uint4v &codes, const uint2v *lut, const_f32_ptr X, int K,
                                             int k0)
 {
 #pragma unroll 1

@@ -76,21 +76,15 @@ __device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *
                                           int k_zero, int g)
 {
     constexpr int CH = Geo<G>::CH, SH = Geo<G>::SH;
-    for (int c = CH; c <= n; c += CH) {
-        const int4v cur = q;
-        q = *reinterpret_cast<const int4v_unaligned *>(p + c);
-        float4v v[4];
-        gather4<SH>(v, cur, base);
+    // one loop for whole and partly filled steps: the accumulator is touched in one place only
+    for (int c = 0; c < n; c += CH) {
+        int4v cur = q;
+        if (c + CH < n) q = *reinterpret_cast<const int4v_unaligned *>(p + c + CH);
+        if (c + CH > n) {   // the last, partly filled step (wave-uniform)
+            const int rem = n - c;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if constexpr (NEG) acc -= v[t]; else acc += v[t];
+            for (int t = 0; t < 4; ++t) cur[t] = (4 * g + t < rem) ? cur[t] : k_zero;
         }
-    }
-    const int rem = n & (CH - 1);
-    if (n > 0 && rem) {
-        int4v cur;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) cur[t] = (4 * g + t < rem) ? q[t] : k_zero;
         float4v v[4];
         gather4<SH>(v, cur, base);
 #pragma unroll
