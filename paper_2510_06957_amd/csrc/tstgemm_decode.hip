@@ -58,10 +58,18 @@ template <int MM, int MODE, bool CHUNKED>
 __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__restrict__ rows, int &p, int p1, int k_hi,
                                             int k_zero, const float *xs, int k_lo, int kc1, int lane)
 {
+    // The 16 bytes of a lane for the round that starts at entry `at`.  The load is unconditional (so that the next
+    // round can be in flight while this one is gathered): lanes behind the end of the list read the piece at its
+    // end instead (the arrays have that much slack), and every slot outside [p, p1) is masked below anyway.
+    const int last_piece = p1 & ~3;
+    auto fetch = [&](int at) {
+        return *reinterpret_cast<const int4v *>(rows + min(at + lane * 4, last_piece));
+    };
+    int4v ahead = fetch(p & ~3);
     while (p < p1) {
         const int i = (p & ~3) + lane * 4;
-        int4v q = {0, 0, 0, 0};
-        if (i < p1) q = *reinterpret_cast<const int4v *>(rows + i);
+        const int4v q = ahead;
+        ahead = fetch((p & ~3) + 256);
         int first_late = 4;   // first slot of this lane that belongs to a later chunk
 #pragma unroll
         for (int e = 3; e >= 0; --e) {
