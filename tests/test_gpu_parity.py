@@ -194,6 +194,21 @@ def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density):
         tg.tstgemm_set_tuning(0, 0, 0)
 
 
+@pytest.mark.parametrize("M,K,N,density", [(40, 40000, 70, 0.25), (64, 300, 20000, 0.5), (20, 70000, 33, 0.0625),
+                                           (9, 513, 30000, 0.125)])
+def test_small_tile_long_k_and_wide_n(M, K, N, density):
+    """The small-tile path with many blocks of K per workgroup (more than eight K slices' worth) and with thousands of
+    column groups."""
+    W, X, b = si.make_inputs(M, K, N, density, "normal", seed=71 + M)
+    _, Xi, _ = si.make_inputs(M, K, N, density, "int8", seed=72 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+
+
 @pytest.mark.parametrize("M,K,N", [(70, 130, 67), (300, 516, 100), (6, 130, 40), (40, 130, 67)])
 def test_unaligned_operands(M, K, N):
     """X, b and Y that start 4 bytes off a 16-byte boundary (views into larger tensors): the element-wise paths."""
@@ -287,3 +302,38 @@ def test_decode_k_chunks(M, K, N):
     Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
     Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h)
     assert_exact(Yi, Ydi, f"decode chunks integer {M}x{K}x{N}")
+
+
+@pytest.mark.parametrize("M", [4, 40, 300])
+def test_calls_can_be_captured_in_a_hip_graph(M):
+    """tstgemm() enqueues kernels only (no allocation, no host synchronisation, no memset), so a stream capture
+    records it; every replay, with new contents of X in the same buffer and eager work in between, must give
+    the eager result bit for bit."""
+    import torch
+    K, N = 700, 200
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=81 + M)
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    Xd = torch.from_numpy(X).cuda()
+    bd = torch.from_numpy(b).cuda()
+    Yg = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    tg.tstgemm(Xd, t, bd, Yg)                       # first call outside the capture (one-time kernel attributes)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tg.tstgemm(Xd, t, bd, Yg, stream=side)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(82)
+    for rep in range(4):
+        Xn = rng.standard_normal((M, K)).astype(np.float32)
+        Xd.copy_(torch.from_numpy(Xn).cuda())
+        Yg.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        Ye = tg.tstgemm(Xd, t, bd)                  # eager, same inputs
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, Ye), f"replay {rep}"
+        Yd, A, _ = oracle.tstgemm(Xn, oracle.tcsc_build(W), b)
+        assert_close(Yg.cpu().numpy(), Yd, A, f"graph replay {rep}")
