@@ -93,6 +93,25 @@ def test_variant_long_k_and_wide_n(variant, M, K, N, density):
     assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
 
 
+@pytest.mark.parametrize("k_parts", [0, 1, 2, 3, 8])
+@pytest.mark.parametrize("M,K,N", [(8, 4100, 70), (2, 6000, 200), (5, 1300, 64)])
+def test_packed_k_parts(k_parts, M, K, N):
+    """The packed kernel with K dealt to several workgroups per column group (sums combined by the reduction kernel)
+    and without, also where K is too short for the number of parts asked for."""
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=560 + M)
+    _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=561 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A = oracle.tstgemm_packed(X, oracle.pack5(W), b, K)
+    try:
+        tg.tstgemm_set_tuning(0, k_parts, 0)
+        Y, h = run(tg.tstgemm_packed, W, X, b)
+        assert_close(Y, Yd, A, f"k_parts={k_parts}")
+        Yi, _ = run(tg.tstgemm_packed, W, Xi, b, handle=h)
+        assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+
+
 def test_variant_degenerate_matrices():
     K, N, M = 150, 40, 3
     _, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=530)
