@@ -29,10 +29,13 @@ PEAK_ALU_ADD_TFLOPS = 157.3 / 2
 PEAK_HBM_GBS = 8000.0
 PEAK_ALU_INSTR_T = 256 * 64 * 2.4e9 / 1e12     # vector lane-instructions per second (an FMA counts once)
 
-# HBM bytes of one launch of the main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
-# (profiles/tstgemm_C2_hbm_traffic.md), each counter scaled by what it reads for a copy kernel of known size in the
-# same run.  None where no counter run has been made.
-MEASURED_TRAFFIC = {"C2": (12448 + 32768) * 1024}
+# HBM bytes (read + written) of one launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (profiles/tstgemm_C2_hbm_traffic.md, profiles/hbm_traffic_other_workloads.md), each counter scaled by what it
+# reads for a copy kernel of known size in the same run.  Keyed by (workload, variant); None where no counter run exists.
+MEASURED_TRAFFIC = {
+    ("C2", "tcsc"): 46384230, ("C5a", "tcsc"): 1198020198, ("M64-K16384-N4096-d0.5", "tcsc"): 156667904,
+    ("C4-1", "tcsc"): 91557581, ("C4-8", "tcsc"): 92389990, ("C4-1", "packed"): 9611264, ("C4-8", "packed"): 11882291,
+}
 
 
 def cpu_baseline(W, X, b, nnz, variant="tcsc", budget_s=10.0):
@@ -175,7 +178,7 @@ def main():
 
     decode = wl.M <= 8          # the library's rules for its decode kernel ...
     small = 8 < wl.M <= 64      # ... and its small-tile kernel
-    traffic = MEASURED_TRAFFIC.get(wl.name)
+    traffic = MEASURED_TRAFFIC.get((wl.name, args.variant))
     if args.variant == "packed":
         # dense decode: every entry of the padded W costs one conversion and M multiply-adds on the vector ALUs
         # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s); the codes are 1.6 bits per entry
