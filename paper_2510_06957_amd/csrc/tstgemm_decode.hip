@@ -176,6 +176,10 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Ac
     int grid = compute_units() * per_cu;
     const int need = (t->N + kDecodeWaves - 1) / kDecodeWaves;
     if (grid > need) grid = need;
+    // every wavefront takes the same number of columns, one after the other: with 1.3 columns per wavefront a full grid
+    // would leave two thirds of the wavefronts (and of the loads in flight) idle during the second round
+    const int rounds = (need + grid - 1) / grid;
+    grid = (need + rounds - 1) / rounds;
     hipError_t e;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((k_decode<MM, CHUNKED, SIGNED>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
