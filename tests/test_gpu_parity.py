@@ -209,6 +209,21 @@ def test_small_tile_long_k_and_wide_n(M, K, N, density):
     assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
 
 
+@pytest.mark.parametrize("M", [3, 40, 130, 300])
+def test_very_long_k(M):
+    """K = 100000 (1563 K-blocks, 391 list cuts, several LDS chunks of the decode kernel) with a handful of columns:
+    every path with far more blocks of K per workgroup than any benchmark shape has."""
+    K, N = 100000, 70
+    W, X, b = si.make_inputs(M, K, N, 0.25, "normal", seed=91 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    Xi = si.draw_dense(np.random.Generator(np.random.PCG64(92)), X.shape, "int8")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+
+
 @pytest.mark.parametrize("M,K,N", [(70, 130, 67), (300, 516, 100), (6, 130, 40), (40, 130, 67)])
 def test_unaligned_operands(M, K, N):
     """X, b and Y that start 4 bytes off a 16-byte boundary (views into larger tensors): the element-wise paths."""
