@@ -155,3 +155,23 @@ def test_other_encodings_match_the_oracle(K, N, density):
     assert np.array_equal(cs, ocs) and np.array_equal(idx, oidx)
     assert np.array_equal(tg.tcsc_packed_codes(t), oracle.pack5(W))
     assert np.array_equal(oracle.unpack5(tg.tcsc_packed_codes(t), K), W)
+
+
+def test_random_small_matrices_round_trip():
+    """Many small random ternary matrices of random shape and density, including empty and full ones: the library's
+    builder, its three exporters and from_arrays/to_dense against the oracle's construction and the matrix itself."""
+    rng = np.random.default_rng(2025)
+    for _ in range(200):
+        K, N = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        density = float(rng.choice([0.0, 0.1, 0.5, 0.9, 1.0]))
+        u = rng.random((K, N))
+        W = np.where(u < density / 2, 1, np.where(u < density, -1, 0)).astype(np.int8)
+        t = tg.tcsc_build(W)
+        o = oracle.tcsc_build(W)
+        arrays = tg.tcsc_arrays(t)
+        for a, e in zip(arrays, (o.col_start_pos, o.col_start_neg, o.row_index_pos, o.row_index_neg)):
+            assert np.array_equal(a, e)
+        assert np.array_equal(tg.tcsc_to_dense(tg.tcsc_from_arrays(*arrays, K, N)), W)
+        cs, idx = tg.tcsc_signed_arrays(t)
+        assert np.array_equal(oracle.signed_to_dense(cs, idx, K), W)
+        assert np.array_equal(oracle.unpack5(tg.tcsc_packed_codes(t), K), W)
