@@ -185,17 +185,18 @@ int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, in
  * through a 243-entry table (as in the paper) into five weights, and ALL entries take part in the sum,
  * the zeros as x * 0.  Unlike every other entry point this one therefore reads X entries whose weight is
  * zero: X must be finite.  Products with -1, 0, +1 are exact, so the rounding is that of the additions,
- * in an order fixed by (M, K, N).  Arguments otherwise as for tstgemm().  Errors: as tstgemm(), and
- * EINVAL for M > 8.
+ * in an order fixed by (M, K, N) and the tuning parameters.  Arguments otherwise as for tstgemm() (it may
+ * use the handle's workspace, so calls on one handle must be ordered).  Errors: as tstgemm(), and EINVAL
+ * for M > 8.
  */
 int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
  * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront
  * (1, 2 or 4; the small-tile kernel has 1 and 2 and takes 4 as 2), number of K slices (1..8) computed by
- * different workgroups and summed in a fixed order, and the largest number of row tiles of X packed and
- * processed at a time (>= 1, large-M path only).  0 restores the built-in choice for that parameter.
- * Process-wide.
+ * different workgroups and summed in a fixed order (also the number of workgroups per column group of
+ * tstgemm_packed()), and the largest number of row tiles of X packed and processed at a time (>= 1,
+ * large-M path only).  0 restores the built-in choice for that parameter.  Process-wide.
  * Errors: EINVAL for a value outside the ranges above.
  */
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
