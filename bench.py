@@ -220,6 +220,11 @@ def main():
     roof["kernel_ms"] = kernel_ms
     roof["kernel_ms_event_pair"] = kernel_raw_ms     # as read from the event pair ...
     roof["empty_event_pair_ms"] = pair_ms            # ... minus what an empty pair reads = kernel_ms
+    # HBM side of the same launch: measured bytes (counter runs) if there are any, else the algorithmic bytes
+    hbm_bytes = traffic if traffic is not None else alg_bytes
+    roof["hbm_gb_per_s"] = hbm_bytes / (kernel_ms * 1e-3) / 1e9
+    roof["hbm_frac"] = roof["hbm_gb_per_s"] / PEAK_HBM_GBS
+    roof["hbm_bytes_are"] = "measured (traffic)" if traffic is not None else "algorithmic"
     roof["algorithmic_adds_per_launch"] = adds
     roof["algorithmic_bytes_per_launch"] = alg_bytes
     # the same accounting for the whole call (packing pre-pass + main kernel + split-K reduction)
