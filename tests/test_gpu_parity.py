@@ -209,6 +209,22 @@ def test_small_tile_long_k_and_wide_n(M, K, N, density):
     assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
 
 
+def test_very_tall_x():
+    """M = 70000 rows against a small matrix: hundreds of row tiles, several of them per workgroup column."""
+    M, K, N = 70000, 70, 33
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=95)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    try:
+        tg.tstgemm_set_tuning(0, 0, 3)      # the same through slabs of three row tiles; K is then sliced, which is
+        Y3, _ = gpu_tstgemm(W, X, b, handle=h)   # another summation order: the oracle is the yardstick again
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+    assert_close(Y3, Yd, A, f"{M}x{K}x{N} in slabs")
+
+
 @pytest.mark.parametrize("M", [3, 40, 130, 300])
 def test_very_long_k(M):
     """K = 100000 (1563 K-blocks, 391 list cuts, several LDS chunks of the decode kernel) with a handful of columns:
