@@ -72,7 +72,7 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
 /*
  * Where things are inside the device buffer, byte offsets from its start.  The buffer holds
  * the four TCSC arrays unchanged (read by the small-M and small-tile kernels; each index array is
- * followed by 32 entries of slack, which those kernels may load but never use), their K-blocked
+ * followed by 64 entries of slack, which those kernels may load but never use), their K-blocked
  * form (read by the large-M kernel) and the workspace of tstgemm().  K-blocking follows the idea
  * of BlockedTCSC (Sec. 3, "Blocking"): the rows [0,K) are cut into blocks of k_block = 64 rows
  * so that all X entries one block touches fit in the LDS, every column's two lists are cut at
@@ -91,7 +91,7 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *   signed_index int32 [nnz_pos + nnz_neg]    the "inverted index" form (Sec. 3): the two lists of a column merged in
  *                                             ascending row order, +1 in row i stored as i, -1 as ~i; column n's
  *                                             entries are [col_start_pos[n] + col_start_neg[n],
- *                                             col_start_pos[n+1] + col_start_neg[n+1]); 32 entries of slack behind it.
+ *                                             col_start_pos[n+1] + col_start_neg[n+1]); 64 entries of slack behind it.
  *                                             Read by tstgemm_signed().
  *   packed     uint8  [n_chunks5][n_pad][16]  the "value compression" form (Sec. 3): five consecutive rows of a
  *                                             column in one byte (see tcsc_packed_codes() for the code); group g

@@ -26,7 +26,7 @@ void compute_layout(tcsc *t)
     auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     l.off_col_start_pos = place(sizeof(int32_t) * (size_t)(t->N + 1));
     l.off_col_start_neg = place(sizeof(int32_t) * (size_t)(t->N + 1));
-    // + slack: the kernels read the lists in groups of up to 32 entries
+    // + slack: the kernels read the lists in groups of up to 64 entries
     l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + tst::kIndexSlack));
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + tst::kIndexSlack));
     l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);

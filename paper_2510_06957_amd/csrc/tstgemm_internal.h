@@ -13,7 +13,7 @@ namespace tst {
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
 constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
-constexpr int kIndexSlack = 32;   // entries behind each index array that may be read (never used)
+constexpr int kIndexSlack = 64;   // entries behind each index array that may be read (never used)
 constexpr int kChunk5 = 16;       // groups of five rows (bytes) per column and chunk of the value-compression form
 constexpr size_t kPartialBytes = (size_t)32 << 20;       // split-K partial sums: workgroup tiles [tile][slice][column][row] fp32
 constexpr size_t kXtMinBytes = (size_t)128 << 20;        // room for the tiled, transposed copy of X (a slab of rows at a time)
@@ -84,13 +84,13 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream);
 // tstgemm_side.hip -- X packing pre-pass and split-K reduction, shared by the tiled paths.
 constexpr int kMaxKSlices = 8;
 int compute_units();
-// X (rows x K, row-major) -> xt[tile][k_pad][TM] (TM = 64, 128 or 256 rows per tile, or one tile of 32; k_pad a
+// X (rows x K, row-major) -> xt[tile][k_pad][TM] (TM = 64, 128 or 256 rows per tile, or one tile of 32 or 16; k_pad a
 // multiple of 64), zero padded.
 hipError_t launch_pack(const float *X, float *xt, int rows, int K, int k_pad, int TM, hipStream_t stream);
 // Y = sum of the k_slices partial tiles ([tile][slice][C columns][TM rows], C = 16, 32 or 64) in slice order + b, then act.
 hipError_t launch_reduce(int C, const float *partials, const float *b, const Activation &act, float *Y, int M, int N,
                          int m_tiles, int n_colgroups, int k_slices, int TM, hipStream_t stream);
-// tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (one tile of 64 or 32 rows).
+// tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (one tile of 64, 32 or 16 rows).
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream);
 // tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 64.

@@ -45,7 +45,7 @@ k_pack_x(const float *__restrict__ X, float *__restrict__ xt, int rows, int K, i
     }
     __syncthreads();
     const int kk = threadIdx.x >> 2, q = threadIdx.x & 3;
-    if (16 * q >= TM) return;   // TM = 32: one tile, the upper half of the 64 rows does not exist
+    if (16 * q >= TM) return;   // TM = 32 or 16: one tile, the rows beyond it do not exist
     const int tile = m0 / TM, r0 = m0 % TM;
     float *dst = xt + ((size_t)tile * k_pad + (size_t)kb * 64 + kk) * TM + r0 + 16 * q;
 #pragma unroll
@@ -146,7 +146,7 @@ int compute_units()
 
 hipError_t launch_pack(const float *X, float *xt, int rows, int K, int k_pad, int TM, hipStream_t stream)
 {
-    if (TM < 64 && (TM != 32 || rows > TM)) return hipErrorInvalidValue;   // 32-row tiles: a single tile only
+    if (TM < 64 && ((TM != 32 && TM != 16) || rows > TM)) return hipErrorInvalidValue;   // short tiles: a single tile only
     const long long chunks = TM < 64 ? 1 : ((long long)rows + TM - 1) / TM * (TM / 64);
     if (chunks > 65535 || k_pad % 64 != 0) return hipErrorInvalidValue;
     const bool vec = (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);

@@ -4,8 +4,8 @@
 // the end; no multiplications.  With at most 64 rows of X a wavefront has more lanes than rows, so the mapping
 // differs from the large-M kernel's:
 //
-//   * the 64 lanes form G groups (G = 4 for M <= 64, 8 for M <= 32); a lane owns 4 consecutive rows of X, a group all
-//     TM = 256 / G rows of the tile;
+//   * the 64 lanes form G groups (G = 4 for M <= 64, 8 for M <= 32, 16 for M <= 16); a lane owns 4 consecutive rows of
+//     X, a group all TM = 256 / G rows of the tile;
 //   * the G groups take G consecutive members of the SAME list at a time (the paper's "horizontal" scheme, Sec. 3,
 //     between the groups; its "vertical" scheme inside a group): one ds_read_b128 of the wavefront gathers G tile
 //     rows, one per group, and every group keeps its own partial sums, which are added across the groups once, at the
@@ -16,7 +16,7 @@
 //     row numbers with one 16-byte load, 4 G per wavefront, one load ahead of their use; a row number costs one VALU
 //     instruction (shift and add to the lane's LDS address) and no scalar work;
 //   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of the packed X tile in the LDS (64 KiB:
-//     256 rows of W at TM = 64, 512 at TM = 32; tile[k][TM]) with a row of zeros in front of it for the slots behind
+//     256 rows of W at TM = 64, 512 at TM = 32, 1024 at TM = 16; tile[k][TM]) with a row of zeros in front of it for the slots behind
 //     the end of a slice; two workgroups share a compute unit, one computes while the other exchanges its tile;
 //   * split K, packing pre-pass and reduction as in the large-M path.
 #include "tstgemm_internal.h"
@@ -39,10 +39,11 @@ template <int G> struct Geo {
     static constexpr int L = 64 / G;            // lanes per group
     static constexpr int TM = 4 * L;            // rows of X per tile
     static constexpr int RB = TM * 4;           // bytes of a tile row
-    static constexpr int SH = G == 4 ? 8 : 7;   // log2(RB)
+    static constexpr int SH = G == 4 ? 8 : G == 8 ? 7 : 6;   // log2(RB)
     static constexpr int ROWS = STAGE / RB;     // rows of W per block
     static constexpr int CUTS = ROWS / kCutRows;   // list cuts per block
     static constexpr int CH = 4 * G;            // list entries per wavefront and step
+    static constexpr int PR = TM < 32 ? 32 : TM;   // rows of a partial tile (the reduction kernel works in units of 32 rows)
     static_assert((1 << SH) == RB && CH <= kIndexSlack, "geometry");
 };
 
@@ -53,7 +54,7 @@ struct SmallArgs {
     const float *b;
     const float *alpha;
     float *Y;
-    float *partials;            // [colgroup][k_slices][16 NCW columns][TM rows] when k_slices > 1
+    float *partials;            // [colgroup][k_slices][16 NCW columns][PR rows] when k_slices > 1
     int M, N, n_pad, n_cuts, n_blocks, n_colgroups, k_slices, blocks_per_slice;
     int remap, alpha_stride;
 };
@@ -190,11 +191,13 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 
     if (a.k_slices > 1) {
         // this K slice's partial tile for k_reduce, [column][row]: group 0 stores TM contiguous floats per column
-        constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
-        float *dst = a.partials + ((size_t)cg * a.k_slices + slice) * kTileFloats + (size_t)(wave * NCW) * TM + r * 4;
+        // (columns PR floats apart; rows TM .. PR - 1, if any, are never looked at)
+        constexpr int PR = geo::PR;
+        constexpr size_t kTileFloats = (size_t)NW * NCW * PR;
+        float *dst = a.partials + ((size_t)cg * a.k_slices + slice) * kTileFloats + (size_t)(wave * NCW) * PR + r * 4;
         if (g == 0) {
 #pragma unroll
-            for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<float4v *>(dst + (size_t)j * TM));
+            for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<float4v *>(dst + (size_t)j * PR));
         }
         return;
     }
@@ -233,7 +236,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     a.n_colgroups = l.n_pad / (NW * NCW);
     if (k_slices > n_blocks) k_slices = n_blocks;
     if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
-    const size_t slice_bytes = (size_t)a.n_colgroups * NW * NCW * TM * sizeof(float);
+    const size_t slice_bytes = (size_t)a.n_colgroups * NW * NCW * geo::PR * sizeof(float);
     if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
@@ -246,12 +249,12 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
-    return launch_reduce(NW * NCW, d.partials, b, act, Y, M, l.N, 1, a.n_colgroups, k_slices, TM, stream);
+    return launch_reduce(NW * NCW, d.partials, b, act, Y, M, l.N, 1, a.n_colgroups, k_slices, geo::PR, stream);
 }
 
 }  // namespace
 
-// M <= 64: one tile of 64 rows, or of 32 rows with twice as many rows of W per block.  Two columns per wavefront and
+// M <= 64: one tile of 64 rows, or of 32 / 16 rows with two / four times as many rows of W per block.  Two columns per wavefront and
 // K sliced (at block borders) as far as it takes to give every compute unit two workgroups; a short K (at most four
 // list cuts) is not sliced and takes one column per wavefront instead, which saves the reduction kernel.
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
@@ -267,6 +270,9 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Act
         const int slots = 2 * compute_units();
         k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
     }
+    if (M <= 16)
+        return ncw == 1 ? launch<1, 16>(X, t, b, act, Y, M, k_slices, stream)
+                        : launch<2, 16>(X, t, b, act, Y, M, k_slices, stream);
     if (M <= 32)
         return ncw == 1 ? launch<1, 8>(X, t, b, act, Y, M, k_slices, stream)
                         : launch<2, 8>(X, t, b, act, Y, M, k_slices, stream);
