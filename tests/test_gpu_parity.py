@@ -368,3 +368,32 @@ def test_calls_can_be_captured_in_a_hip_graph(M):
         assert torch.equal(Yg, Ye), f"replay {rep}"
         Yd, A, _ = oracle.tstgemm(Xn, oracle.tcsc_build(W), b)
         assert_close(Yg.cpu().numpy(), Yd, A, f"graph replay {rep}")
+
+
+def test_random_shapes_and_densities():
+    """Eighty seeded random problems (M, K, N, density, with or without bias, any kernel): real inputs within the
+    tolerance, integer inputs bit for bit."""
+    rng = np.random.default_rng(4711)
+    for case in range(80):
+        M = int(rng.choice([rng.integers(1, 9), rng.integers(9, 65), rng.integers(65, 400)]))
+        K = int(rng.choice([rng.integers(1, 70), rng.integers(70, 700), rng.integers(700, 5000)]))
+        N = int(rng.choice([rng.integers(1, 20), rng.integers(20, 300)]))
+        density = float(rng.choice([0.02, 0.125, 0.5, 0.9]))
+        W, X, b = si.make_inputs(M, K, N, density, "normal", seed=5000 + case)
+        if case % 4 == 0:
+            b = None
+        ot = oracle.tcsc_build(W)
+        Yd, A, _ = oracle.tstgemm(X, ot, b)
+        Y, h = gpu_tstgemm(W, X, b)
+        assert_close(Y, Yd, A, f"case {case}: {M}x{K}x{N} d={density}")
+        Xi = si.draw_dense(np.random.Generator(np.random.PCG64(6000 + case)), X.shape, "int8")
+        Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+        assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32)), f"case {case}: {M}x{K}x{N}"
+        if M <= 8:
+            import torch
+            Xd = torch.from_numpy(Xi).cuda()
+            bd = None if b is None else torch.from_numpy(b).cuda()
+            for fn in (tg.tstgemm_signed, tg.tstgemm_packed):
+                Yv = fn(Xd, h, bd)
+                torch.cuda.synchronize()
+                assert np.array_equal(Yv.cpu().numpy(), Yi), f"case {case} {fn.__name__}: {M}x{K}x{N}"
