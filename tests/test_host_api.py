@@ -175,3 +175,42 @@ def test_random_small_matrices_round_trip():
         cs, idx = tg.tcsc_signed_arrays(t)
         assert np.array_equal(oracle.signed_to_dense(cs, idx, K), W)
         assert np.array_equal(oracle.unpack5(tg.tcsc_packed_codes(t), K), W)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/tstgemm.h must be usable from C: it compiles as C99 with all warnings on, and a C program can call
+    the host-side entry points through it (linked against the built library)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "tstgemm.h"
+int main(void)
+{
+    const int8_t W[6] = {1, 0, -1, 0, 1, -1};   /* K = 2, N = 3 */
+    tcsc_t *t = NULL;
+    int K = 0, N = 0;
+    int64_t p = 0, q = 0;
+    size_t bytes = 0;
+    uint8_t codes[3];
+    if (tcsc_build(W, 2, 3, &t) != TSTGEMM_OK) return 1;
+    if (tcsc_dims(t, &K, &N, &p, &q) != TSTGEMM_OK || K != 2 || N != 3 || p != 2 || q != 2) return 2;
+    if (tcsc_device_bytes(t, &bytes) != TSTGEMM_OK || bytes == 0) return 3;
+    if (tcsc_packed_codes(t, codes) != TSTGEMM_OK) return 4;
+    /* column 0 = (1, 0) -> 81; column 1 = (0, 1) -> 27; column 2 = (-1, -1) -> 2*81 + 2*27 = 216 */
+    if (codes[0] != 81 || codes[1] != 27 || codes[2] != 216) return 5;
+    if (tstgemm(NULL, t, NULL, NULL, 1, 2, 3, NULL) != TSTGEMM_EINVAL) return 6;
+    printf("%s\n", tcsc_strerror(TSTGEMM_ENOTUPLOADED));
+    tcsc_destroy(t);
+    return 0;
+}
+''')
+    exe = tmp_path / "use_header"
+    lib = tg.library_path()
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", f"-I{ROOT / 'include'}", str(src), "-o", str(exe),
+           str(lib), f"-Wl,-rpath,{lib.parent}", "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert "tcsc_upload" in r.stdout
