@@ -4,8 +4,9 @@
  * C ABI of libtstgemm.so.  Plain pointers and sizes only; every pointer argument says
  * whether it is HOST or DEVICE memory.  All functions return 0 (TSTGEMM_OK) or a negative
  * TSTGEMM_E* code; tcsc_strerror() turns a code into text.  No function throws, aborts or
- * prints.  Besides what a handle owns the library keeps two pieces of global state: the tuning
- * overrides of tstgemm_set_tuning() and the event pair of tstgemm_profile_events().
+ * prints.  Besides what a handle owns the library keeps three pieces of global state: the tuning
+ * overrides of tstgemm_set_tuning(), the choice of tstgemm_set_decode_lists() and the event pair of
+ * tstgemm_profile_events().
  *
  * The operation is Eq. 1 of the paper (Sec. 2): X is dense fp32 (M x K, row-major), W is a
  * K x N matrix with entries in {-1, 0, +1}, b (N) is added to every row of the product,
@@ -88,6 +89,11 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *                                             is >= c * 256 (c = n_cuts: the end of the list), [c][n][1]: the same
  *                                             for the -1 list.  Rows ascend inside a list, so the piece of a list
  *                                             inside a block of 256 rows is the slice between two cuts.
+ *   col_start16_pos / _neg  int32 [N + 1]     only if K <= 65535 (has_lists16 != 0): the two lists of every column once
+ *   row_index16_pos / _neg  uint16 [nnz16]    more, with 16-bit row numbers and every column's list padded to a multiple of
+ *                                             8 entries (16 bytes) with the value K, which stands for a row of zeros;
+ *                                             col_start16 are the pointers into these padded arrays.  Half the bytes for
+ *                                             the small-M kernel, which is bound by them, and no partly used 16-byte piece.
  *   signed_index int32 [nnz_pos + nnz_neg]    the "inverted index" form (Sec. 3): the two lists of a column merged in
  *                                             ascending row order, +1 in row i stored as i, -1 as ~i; column n's
  *                                             entries are [col_start_pos[n] + col_start_neg[n],
@@ -105,10 +111,13 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  */
 typedef struct tcsc_layout {
     int32_t K, N, n_pad, k_block, n_kblocks, n_cuts;   /* n_cuts = K / 256 rounded up */
-    int32_t n_chunks5, reserved;
+    int32_t n_chunks5, has_lists16;
     int64_t nnz_pos, nnz_neg;
+    int64_t nnz16_pos, nnz16_neg;   /* entries of the padded 16-bit lists (0 without them) */
     size_t off_col_start_pos, off_col_start_neg, off_row_index_pos, off_row_index_neg;
-    size_t off_masks, off_list_cuts, off_signed_index, off_packed, off_workspace, workspace_bytes, total_bytes;
+    size_t off_masks, off_list_cuts;
+    size_t off_col_start16_pos, off_col_start16_neg, off_row_index16_pos, off_row_index16_neg;
+    size_t off_signed_index, off_packed, off_workspace, workspace_bytes, total_bytes;
 } tcsc_layout_t;
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);
@@ -130,7 +139,8 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * X: DEVICE fp32 M*K row-major.  b: DEVICE fp32 N, or NULL for b = 0.  Y: DEVICE fp32 M*N
  * row-major, fully overwritten; must not overlap X, b or the handle's device buffer.
  * M >= 1 arbitrary; K, N must equal the handle's.  M <= 8 takes the small-M kernel (X resident in the LDS, in
- * chunks of K if it is larger than 150 KiB; TCSC lists streamed), 8 < M <= 64 the small-tile kernel (one tile of
+ * chunks of K if it is larger than 150 KiB; TCSC lists streamed -- their padded 16-bit copy where there is one
+ * and X fits the LDS whole), 8 < M <= 64 the small-tile kernel (one tile of
  * X, lists read from the TCSC arrays between the list cuts), everything else the large-M path (row sets).
  * Asynchronous: the kernels are enqueued on `stream` (a hipStream_t, NULL = null stream), no host
  * synchronisation, no allocation.
@@ -200,6 +210,14 @@ int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, in
  * Errors: EINVAL for a value outside the ranges above.
  */
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
+
+/*
+ * Which copy of the lists the small-M kernel of tstgemm() reads when the matrix has both (K <= 65535): 0 (the
+ * default) = the padded 16-bit copy, non-zero = the 32-bit TCSC arrays themselves.  For measurements and tests.  The
+ * two deal the entries of a list to the lanes differently (8 or 4 consecutive ones per lane), so the fp32 rounding can
+ * differ in the last bits; integer-valued inputs give the same, exact result.  Process-wide.  Always returns TSTGEMM_OK.
+ */
+int tstgemm_set_decode_lists(int wide);
 
 /*
  * For benchmarks that must time one kernel: from now on every tstgemm() call records the

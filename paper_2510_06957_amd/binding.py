@@ -24,11 +24,14 @@ class TstgemmError(RuntimeError):
 class TcscLayout(ctypes.Structure):
     _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("n_pad", ctypes.c_int32), ("k_block", ctypes.c_int32),
                 ("n_kblocks", ctypes.c_int32), ("n_cuts", ctypes.c_int32),
-                ("n_chunks5", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("n_chunks5", ctypes.c_int32), ("has_lists16", ctypes.c_int32),
                 ("nnz_pos", ctypes.c_int64), ("nnz_neg", ctypes.c_int64),
+                ("nnz16_pos", ctypes.c_int64), ("nnz16_neg", ctypes.c_int64),
                 ("off_col_start_pos", ctypes.c_size_t), ("off_col_start_neg", ctypes.c_size_t),
                 ("off_row_index_pos", ctypes.c_size_t), ("off_row_index_neg", ctypes.c_size_t),
                 ("off_masks", ctypes.c_size_t), ("off_list_cuts", ctypes.c_size_t),
+                ("off_col_start16_pos", ctypes.c_size_t), ("off_col_start16_neg", ctypes.c_size_t),
+                ("off_row_index16_pos", ctypes.c_size_t), ("off_row_index16_neg", ctypes.c_size_t),
                 ("off_signed_index", ctypes.c_size_t), ("off_packed", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
                 ("workspace_bytes", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
 
@@ -71,6 +74,8 @@ def _load():
     lib.tcsc_strerror.restype = ctypes.c_char_p
     lib.tstgemm_set_tuning.argtypes = [ci, ci, ci]
     lib.tstgemm_set_tuning.restype = ci
+    lib.tstgemm_set_decode_lists.argtypes = [ci]
+    lib.tstgemm_set_decode_lists.restype = ci
     lib.tstgemm_profile_events.argtypes = [vp, vp]
     lib.tstgemm_profile_events.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
@@ -284,6 +289,11 @@ def tcsc_packed_codes(t: Tcsc) -> np.ndarray:
 
 def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0, slab_tiles: int = 0):
     _check(_load().tstgemm_set_tuning(int(cols_per_wave), int(k_slices), int(slab_tiles)), "tstgemm_set_tuning")
+
+
+def tstgemm_set_decode_lists(wide: bool = False):
+    """The small-M kernel reads the 32-bit TCSC lists (True) or their padded 16-bit copy where it can (False, default)."""
+    _check(_load().tstgemm_set_decode_lists(int(bool(wide))), "tstgemm_set_decode_lists")
 
 
 def tstgemm_profile_events(before=None, after=None):

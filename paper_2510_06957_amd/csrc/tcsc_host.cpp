@@ -31,10 +31,38 @@ void compute_layout(tcsc *t)
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + tst::kIndexSlack));
     l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
     l.off_list_cuts = place(2 * sizeof(int32_t) * (size_t)(l.n_cuts + 1) * (size_t)l.n_pad);
+    // padded 16-bit lists: every column's list rounded up to 8 entries; the pad value K must fit in 16 bits
+    l.has_lists16 = t->K <= 65535 ? 1 : 0;
+    l.nnz16_pos = l.nnz16_neg = 0;
+    t->col_start16_pos.clear();
+    t->col_start16_neg.clear();
+    if (l.has_lists16) {
+        auto padded = [&](const std::vector<int32_t> &cs, std::vector<int32_t> &cs16) {
+            cs16.assign((size_t)t->N + 1, 0);
+            int64_t at = 0;
+            for (int n = 0; n < t->N; ++n) {
+                at += ((int64_t)cs[n + 1] - cs[n] + 7) / 8 * 8;
+                if (at > INT32_MAX) return (int64_t)-1;
+                cs16[n + 1] = (int32_t)at;
+            }
+            return at;
+        };
+        l.nnz16_pos = padded(t->col_start_pos, t->col_start16_pos);
+        l.nnz16_neg = padded(t->col_start_neg, t->col_start16_neg);
+        if (l.nnz16_pos < 0 || l.nnz16_neg < 0) {   // the padding does not fit 32-bit pointers: go without
+            l.has_lists16 = 0;
+            l.nnz16_pos = l.nnz16_neg = 0;
+            t->col_start16_pos.clear();
+            t->col_start16_neg.clear();
+        }
+    }
+    l.off_col_start16_pos = place(l.has_lists16 ? sizeof(int32_t) * (size_t)(t->N + 1) : 0);
+    l.off_col_start16_neg = place(l.has_lists16 ? sizeof(int32_t) * (size_t)(t->N + 1) : 0);
+    l.off_row_index16_pos = place(l.has_lists16 ? sizeof(uint16_t) * (size_t)(l.nnz16_pos + tst::kIndexSlack) : 0);
+    l.off_row_index16_neg = place(l.has_lists16 ? sizeof(uint16_t) * (size_t)(l.nnz16_neg + tst::kIndexSlack) : 0);
     l.off_signed_index = place(sizeof(int32_t) * (size_t)(l.nnz_pos + l.nnz_neg + tst::kIndexSlack));
     const int groups5 = (t->K + 4) / 5;
     l.n_chunks5 = (groups5 + tst::kChunk5 - 1) / tst::kChunk5;
-    l.reserved = 0;
     l.off_packed = place((size_t)l.n_chunks5 * (size_t)l.n_pad * tst::kChunk5);
     l.workspace_bytes = tst::workspace_bytes(l.n_kblocks);
     l.off_workspace = place(l.workspace_bytes);
@@ -240,6 +268,10 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
     if (copy(l.off_col_start_neg, t->col_start_neg) != hipSuccess) return TSTGEMM_EHIP;
     if (copy(l.off_row_index_pos, t->row_index_pos) != hipSuccess) return TSTGEMM_EHIP;
     if (copy(l.off_row_index_neg, t->row_index_neg) != hipSuccess) return TSTGEMM_EHIP;
+    if (l.has_lists16) {
+        if (copy(l.off_col_start16_pos, t->col_start16_pos) != hipSuccess) return TSTGEMM_EHIP;
+        if (copy(l.off_col_start16_neg, t->col_start16_neg) != hipSuccess) return TSTGEMM_EHIP;
+    }
     // The sources are pageable host memory: wait until the copies have read them.
     if (hipStreamSynchronize(s) != hipSuccess) return TSTGEMM_EHIP;
     if (tst::launch_reblock(t, s) != hipSuccess) return TSTGEMM_EHIP;
@@ -303,6 +335,12 @@ int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)
     tst::g_cols_per_wave = cols_per_wave;
     tst::g_k_slices = k_slices;
     tst::g_slab_tiles = slab_tiles;
+    return TSTGEMM_OK;
+}
+
+int tstgemm_set_decode_lists(int wide)
+{
+    tst::g_decode_wide_lists = wide != 0;
     return TSTGEMM_OK;
 }
 

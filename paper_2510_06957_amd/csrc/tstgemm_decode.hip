@@ -11,7 +11,11 @@
 //     part of a list that falls into a chunk is contiguous and a cursor per list is enough;
 //   * one wavefront per column; its 64 lanes split the column's +1 list and then its -1 list
 //     (the paper's "horizontal" SIMD scheme, Sec. 3: partial sums per lane, one horizontal sum
-//     at the end), reading 4 consecutive indices per lane with a 16-byte load;
+//     at the end), reading 4 consecutive indices per lane with a 16-byte load -- or 8, from the
+//     padded 16-bit copy of the lists that the upload pass makes when K <= 65535: the kernel is
+//     bound by the bytes of the lists, a row number below 65536 does not need 32 bits, and with
+//     every list padded to whole 16-byte pieces (pad value K, the row of zeros; the paper's
+//     dummy-zero padding, Sec. 3) no entry has to be masked;
 //   * the M per-lane partial sums are folded across the wavefront by a halving exchange, the
 //     bias is added once, last (then the optional PReLU), and one lane per row stores the result.
 // The same kernel also runs on the paper's inverted-index form (Sec. 3): one merged list per column
@@ -25,6 +29,7 @@ constexpr int kDecodeThreads = 1024;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 constexpr int kDecodeMaxLds = 150 * 1024;
 typedef int int4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 // Butterfly sum over the 64 lanes of each of the MM values; every lane ends with all totals.
 template <int MM> __device__ __forceinline__ void wave_sum(float (&v)[MM])
@@ -99,13 +104,48 @@ __device__ __forceinline__ void run_sublist(float (&acc)[MM], const int32_t *__r
     p = p1;
 }
 
-// SIGNED: rip is the merged list of the inverted-index form (column n at col_start_pos[n] + col_start_neg[n]), rin unused.
-template <int MM, bool CHUNKED, bool SIGNED>
+// A list of the padded 16-bit copy, entries [p, p1), both multiples of 8: a lane takes 8 consecutive entries (16 bytes)
+// per round, a wavefront 512; every entry is a row number or K, the row of zeros, so nothing has to be masked.  All of
+// X is in the LDS (this form is not used with chunks of K).  NEG: subtract.
+template <int MM, bool NEG>
+__device__ __forceinline__ void run_list16(float (&acc)[MM], const uint16_t *__restrict__ rows, int p, int p1, const float *xs,
+                                           int kc1, int lane)
+{
+    if (p >= p1) return;
+    const int last_piece = p1 - 8;
+    auto fetch = [&](int at) {   // unconditional: a lane behind the end reads the last piece again and does not use it
+        return *reinterpret_cast<const uint4v *>(rows + min(at + lane * 8, last_piece));
+    };
+    uint4v ahead = fetch(p);
+    for (int at = p; at < p1; at += 512) {
+        const uint4v q = ahead;
+        ahead = fetch(at + 512);   // the next round is on its way while this one is gathered
+        if (at + lane * 8 < p1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int row = (int)((q[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+#pragma unroll
+                for (int m = 0; m < MM; ++m) {
+                    const float x = xs[xs_at<MM>(row, m, kc1)];
+                    if (NEG) acc[m] -= x; else acc[m] += x;
+                }
+            }
+        }
+    }
+}
+
+// FORM 0: csp / csn / rip / rin are the TCSC arrays; FORM 1: rip is the merged list of the inverted-index form (column
+// n at col_start_pos[n] + col_start_neg[n]), rin unused; FORM 2 (not with CHUNKED): csp / csn / rip / rin are the
+// pointers and the entries of the padded 16-bit copy of the lists.
+template <int MM, bool CHUNKED, int FORM>
 __global__ void __launch_bounds__(kDecodeThreads)
 k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int32_t *__restrict__ csn,
-         const int32_t *__restrict__ rip, const int32_t *__restrict__ rin, const float *__restrict__ b,
+         const void *__restrict__ rip_, const void *__restrict__ rin_, const float *__restrict__ b,
          const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N, int kc)
 {
+    static_assert(!(FORM == 2 && CHUNKED), "the padded 16-bit lists need all of X in the LDS");
+    constexpr bool SIGNED = FORM == 1;
+    const int32_t *rip = static_cast<const int32_t *>(rip_), *rin = static_cast<const int32_t *>(rin_);
     extern __shared__ __attribute__((aligned(16))) float xs[];   // planes of [kc + 1][<= 4], row kc is all zero
     const int kc1 = kc + 1;
     const int lane = threadIdx.x & 63;
@@ -136,6 +176,10 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
         float acc[MM];
 #pragma unroll
         for (int m = 0; m < MM; ++m) acc[m] = 0.f;
+        if constexpr (FORM == 2) {
+            run_list16<MM, false>(acc, static_cast<const uint16_t *>(rip_), pp, pp1, xs, kc1, lane);
+            run_list16<MM, true>(acc, static_cast<const uint16_t *>(rin_), pn, pn1, xs, kc1, lane);
+        } else
         for (int c = 0; c < n_chunks; ++c) {
             if (CHUNKED) {
                 __syncthreads();   // everybody is done with the previous chunk
@@ -160,14 +204,14 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
     }
 }
 
-template <int MM, bool CHUNKED, bool SIGNED>
+template <int MM, bool CHUNKED, int FORM>
 hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int kc, size_t lds,
                          hipStream_t stream)
 {
     const DeviceTcsc d = device_view(t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM, CHUNKED, SIGNED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM, CHUNKED, FORM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -182,36 +226,42 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Ac
     grid = (need + rounds - 1) / rounds;
     hipError_t e;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_decode<MM, CHUNKED, SIGNED>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, d.col_start_pos,
-                       d.col_start_neg, SIGNED ? d.signed_index : d.row_index_pos, d.row_index_neg, b, act.alpha,
-                       act.alpha_stride, Y, t->K, t->N, kc);
+    const int32_t *cs_pos = FORM == 2 ? d.col_start16_pos : d.col_start_pos;
+    const int32_t *cs_neg = FORM == 2 ? d.col_start16_neg : d.col_start_neg;
+    const void *lists_pos = FORM == 1 ? static_cast<const void *>(d.signed_index)
+                            : FORM == 2 ? static_cast<const void *>(d.row_index16_pos)
+                                        : static_cast<const void *>(d.row_index_pos);
+    const void *lists_neg = FORM == 2 ? static_cast<const void *>(d.row_index16_neg) : static_cast<const void *>(d.row_index_neg);
+    hipLaunchKernelGGL((k_decode<MM, CHUNKED, FORM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, cs_pos, cs_neg,
+                       lists_pos, lists_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N, kc);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     return e;
 }
 
-template <int MM, bool SIGNED>
+template <int MM, int FORM>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
 {
     const int kc = t->K < chunk_rows<MM>() ? t->K : chunk_rows<MM>();
     const size_t lds = (size_t)(kc + 1) * MM * sizeof(float);
-    return t->K > kc ? launch_kernel<MM, true, SIGNED>(X, t, b, act, Y, kc, lds, stream)
-                     : launch_kernel<MM, false, SIGNED>(X, t, b, act, Y, kc, lds, stream);
+    if (t->K > kc)   // K in chunks: the 32-bit lists (the padded 16-bit ones are for X whole in the LDS)
+        return launch_kernel<MM, true, FORM == 2 ? 0 : FORM>(X, t, b, act, Y, kc, lds, stream);
+    return launch_kernel<MM, false, FORM>(X, t, b, act, Y, kc, lds, stream);
 }
 
-template <bool SIGNED>
+template <int FORM>
 hipError_t launch_m(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                     hipStream_t stream)
 {
     switch (M) {
-    case 1: return launch<1, SIGNED>(X, t, b, act, Y, stream);
-    case 2: return launch<2, SIGNED>(X, t, b, act, Y, stream);
-    case 3: return launch<3, SIGNED>(X, t, b, act, Y, stream);
-    case 4: return launch<4, SIGNED>(X, t, b, act, Y, stream);
-    case 5: return launch<5, SIGNED>(X, t, b, act, Y, stream);
-    case 6: return launch<6, SIGNED>(X, t, b, act, Y, stream);
-    case 7: return launch<7, SIGNED>(X, t, b, act, Y, stream);
-    case 8: return launch<8, SIGNED>(X, t, b, act, Y, stream);
+    case 1: return launch<1, FORM>(X, t, b, act, Y, stream);
+    case 2: return launch<2, FORM>(X, t, b, act, Y, stream);
+    case 3: return launch<3, FORM>(X, t, b, act, Y, stream);
+    case 4: return launch<4, FORM>(X, t, b, act, Y, stream);
+    case 5: return launch<5, FORM>(X, t, b, act, Y, stream);
+    case 6: return launch<6, FORM>(X, t, b, act, Y, stream);
+    case 7: return launch<7, FORM>(X, t, b, act, Y, stream);
+    case 8: return launch<8, FORM>(X, t, b, act, Y, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -223,12 +273,14 @@ bool decode_supported(int M) { return M <= 8; }
 hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                          hipStream_t stream)
 {
-    return launch_m<false>(X, t, b, act, Y, M, stream);
+    // the padded 16-bit copy of the lists, if the matrix has one (K <= 65535): half the bytes
+    if (t->layout.has_lists16 && !g_decode_wide_lists) return launch_m<2>(X, t, b, act, Y, M, stream);
+    return launch_m<0>(X, t, b, act, Y, M, stream);
 }
 
 hipError_t launch_decode_signed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
 {
-    return launch_m<true>(X, t, b, Activation{nullptr, 0}, Y, M, stream);
+    return launch_m<1>(X, t, b, Activation{nullptr, 0}, Y, M, stream);
 }
 
 }  // namespace tst

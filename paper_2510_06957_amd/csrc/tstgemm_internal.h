@@ -38,6 +38,7 @@ __device__ __forceinline__ float activate(float v, const float *alpha, int alpha
 struct tcsc {
     int K = 0, N = 0;
     std::vector<int32_t> col_start_pos, col_start_neg, row_index_pos, row_index_neg;
+    std::vector<int32_t> col_start16_pos, col_start16_neg;   // pointers of the padded 16-bit lists (K <= 65535 only)
     tcsc_layout_t layout{};
     void *dev = nullptr;   // caller's device buffer (borrowed) once uploaded
     bool uploaded = false;
@@ -50,6 +51,8 @@ struct DeviceTcsc {
     const int32_t *col_start_pos, *col_start_neg, *row_index_pos, *row_index_neg;
     unsigned long long *masks;   // [n_kblocks][n_pad][2]
     int32_t *list_cuts;          // [n_cuts + 1][n_pad][2]
+    const int32_t *col_start16_pos, *col_start16_neg;   // the padded 16-bit lists (K <= 65535 only) ...
+    uint16_t *row_index16_pos, *row_index16_neg;        // ... pad value K = the row of zeros
     int32_t *signed_index;       // merged lists, -1 entries as ~row
     uint8_t *packed;             // [n_chunks5][n_pad][16] base-3 codes
     float *partials;     // split-K partial sums
@@ -67,6 +70,10 @@ inline DeviceTcsc device_view(const tcsc *t)
                       reinterpret_cast<const int32_t *>(d + l.off_row_index_neg),
                       reinterpret_cast<unsigned long long *>(d + l.off_masks),
                       reinterpret_cast<int32_t *>(d + l.off_list_cuts),
+                      reinterpret_cast<const int32_t *>(d + l.off_col_start16_pos),
+                      reinterpret_cast<const int32_t *>(d + l.off_col_start16_neg),
+                      reinterpret_cast<uint16_t *>(d + l.off_row_index16_pos),
+                      reinterpret_cast<uint16_t *>(d + l.off_row_index16_neg),
                       reinterpret_cast<int32_t *>(d + l.off_signed_index),
                       reinterpret_cast<uint8_t *>(d + l.off_packed),
                       reinterpret_cast<float *>(d + l.off_workspace),
@@ -97,6 +104,7 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Act
 hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream);
 extern int g_cols_per_wave, g_k_slices, g_slab_tiles;   // tuning overrides, 0 = built-in choice
+extern int g_decode_wide_lists;                         // != 0: the small-M kernel reads the 32-bit lists even if 16-bit ones exist
 extern hipEvent_t g_event_before, g_event_after;       // recorded around the main kernel of a call when set
 // tstgemm_decode.hip -- small-M kernel (M <= 8; X in the LDS, in chunks of K if need be).
 bool decode_supported(int M);

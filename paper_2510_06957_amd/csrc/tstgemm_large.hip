@@ -36,7 +36,7 @@
 
 namespace tst {
 
-int g_cols_per_wave = 0, g_k_slices = 0, g_slab_tiles = 0;
+int g_cols_per_wave = 0, g_k_slices = 0, g_slab_tiles = 0, g_decode_wide_lists = 0;
 hipEvent_t g_event_before = nullptr, g_event_after = nullptr;
 
 namespace {

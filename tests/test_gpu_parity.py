@@ -397,3 +397,28 @@ def test_random_shapes_and_densities():
                 Yv = fn(Xd, h, bd)
                 torch.cuda.synchronize()
                 assert np.array_equal(Yv.cpu().numpy(), Yi), f"case {case} {fn.__name__}: {M}x{K}x{N}"
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 300, 70), (8, 513, 65), (3, 4096, 200), (8, 8229, 70), (1, 30000, 40),
+                                   (5, 65535, 33), (2, 65536, 20), (4, 70000, 9)])
+def test_decode_list_widths(M, K, N):
+    """The small-M kernel on the padded 16-bit copy of the lists (K <= 65535, X whole in the LDS) and on the 32-bit TCSC
+    arrays: both within tolerance of the oracle, integer inputs bit for bit; K in chunks or beyond 16 bits takes the
+    32-bit arrays either way."""
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=97 + M)
+    _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=98 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Ydi = oracle.tstgemm(Xi, ot, b)[0].astype(np.float32)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert tg.tcsc_layout(h).has_lists16 == (1 if K <= 65535 else 0)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    assert np.array_equal(gpu_tstgemm(W, Xi, b, handle=h)[0], Ydi)
+    try:
+        tg.tstgemm_set_decode_lists(True)
+        Yw, _ = gpu_tstgemm(W, X, b, handle=h)
+        Ywi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    finally:
+        tg.tstgemm_set_decode_lists(False)
+    assert_close(Yw, Yd, A, f"{M}x{K}x{N}, 32-bit lists")
+    assert np.array_equal(Ywi, Ydi)

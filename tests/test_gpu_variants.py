@@ -39,8 +39,21 @@ def test_device_forms_match_the_oracle(K, N, density):
     W, _, _ = si.make_inputs(1, K, N, density, "uniform", seed=400 + K + N)
     t = tg.tcsc_upload(tg.tcsc_build(W))
     lay = tg.tcsc_layout(t)
-    _, oidx = oracle.signed_build(oracle.tcsc_build(W))
+    ot = oracle.tcsc_build(W)
+    _, oidx = oracle.signed_build(ot)
     assert np.array_equal(device_section(t, lay.off_signed_index, lay.nnz_pos + lay.nnz_neg, np.int32), oidx)
+    # padded 16-bit lists: column n's list at [col_start16[n], col_start16[n + 1]), a multiple of 8 long, the pad is K
+    assert lay.has_lists16 == 1
+    for cs, ri, off_cs, off_ri, nnz16 in ((ot.col_start_pos, ot.row_index_pos, lay.off_col_start16_pos, lay.off_row_index16_pos, lay.nnz16_pos),
+                                          (ot.col_start_neg, ot.row_index_neg, lay.off_col_start16_neg, lay.off_row_index16_neg, lay.nnz16_neg)):
+        cs16 = device_section(t, off_cs, N + 1, np.int32)
+        ri16 = device_section(t, off_ri, nnz16, np.uint16)
+        assert cs16[0] == 0 and cs16[N] == nnz16 and not (cs16 % 8).any()
+        for n in range(N):
+            col = ri[cs[n]:cs[n + 1]]
+            got = ri16[cs16[n]:cs16[n + 1]]
+            assert got.size == -(-col.size // 8) * 8
+            assert np.array_equal(got[:col.size], col) and np.all(got[col.size:] == K)
     # packed[chunk][column][16]: group g of column n is byte [g // 16][n][g % 16]; padding groups and columns are 0
     dev = device_section(t, lay.off_packed, lay.n_chunks5 * lay.n_pad * 16, np.uint8).reshape(lay.n_chunks5, lay.n_pad, 16)
     codes = oracle.pack5(W)                                       # [N][G]

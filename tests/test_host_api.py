@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
             "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tcsc_signed_arrays", "tcsc_packed_codes",
-            "tstgemm_signed", "tstgemm_packed", "tstgemm_set_tuning", "tstgemm_profile_events", "tcsc_destroy",
+            "tstgemm_signed", "tstgemm_packed", "tstgemm_set_tuning", "tstgemm_set_decode_lists",
+            "tstgemm_profile_events", "tcsc_destroy",
             "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
@@ -122,12 +123,22 @@ def test_layout_bookkeeping():
     assert (lay.nnz_pos, lay.nnz_neg) == (int((W == 1).sum()), int((W == -1).sum()))
     assert lay.n_cuts == 3 and lay.n_chunks5 == 7          # 513 rows: 3 cuts of 256, 103 groups of five in 7 chunks of 16
     offs = [lay.off_col_start_pos, lay.off_col_start_neg, lay.off_row_index_pos, lay.off_row_index_neg,
-            lay.off_masks, lay.off_list_cuts, lay.off_signed_index, lay.off_packed, lay.off_workspace, lay.total_bytes]
+            lay.off_masks, lay.off_list_cuts, lay.off_col_start16_pos, lay.off_col_start16_neg, lay.off_row_index16_pos,
+            lay.off_row_index16_neg, lay.off_signed_index, lay.off_packed, lay.off_workspace, lay.total_bytes]
     assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
     assert lay.total_bytes == tg.tcsc_device_bytes(t)
     assert lay.off_list_cuts - lay.off_masks >= 16 * lay.n_kblocks * lay.n_pad
-    assert lay.off_signed_index - lay.off_list_cuts >= 8 * (lay.n_cuts + 1) * lay.n_pad
+    # the padded 16-bit lists: every column rounded up to 8 entries
+    o = oracle.tcsc_build(W)
+    assert lay.has_lists16 == 1
+    assert lay.nnz16_pos == int((-(-np.diff(o.col_start_pos) // 8) * 8).sum())
+    assert lay.nnz16_neg == int((-(-np.diff(o.col_start_neg) // 8) * 8).sum())
+    assert lay.off_col_start16_pos - lay.off_list_cuts >= 8 * (lay.n_cuts + 1) * lay.n_pad
+    assert lay.off_row_index16_neg - lay.off_row_index16_pos >= 2 * lay.nnz16_pos
+    assert lay.off_signed_index - lay.off_row_index16_neg >= 2 * lay.nnz16_neg
     assert lay.off_packed - lay.off_signed_index >= 4 * (lay.nnz_pos + lay.nnz_neg)
+    wide = tg.tcsc_layout(tg.tcsc_build(np.zeros((65536, 1), np.int8)))       # K itself must fit in 16 bits: no copy here
+    assert wide.has_lists16 == 0 and wide.nnz16_pos == 0 and wide.off_row_index16_neg == wide.off_signed_index
     assert lay.off_workspace - lay.off_packed >= 16 * lay.n_chunks5 * lay.n_pad
     assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
 
