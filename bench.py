@@ -34,7 +34,7 @@ PEAK_ALU_INSTR_T = 256 * 64 * 2.4e9 / 1e12     # vector lane-instructions per se
 # reads for a copy kernel of known size in the same run.  Keyed by (workload, variant); None where no counter run exists.
 MEASURED_TRAFFIC = {
     ("C2", "tcsc"): 46384230, ("C5a", "tcsc"): 1198020198, ("M64-K16384-N4096-d0.5", "tcsc"): 156667904,
-    ("C4-1", "tcsc"): 91557581, ("C4-8", "tcsc"): 92389990, ("C4-1", "packed"): 9611264, ("C4-8", "packed"): 11882291,
+    ("C4-1", "tcsc"): 46066176, ("C4-8", "tcsc"): 47349248, ("C4-1", "packed"): 9611264, ("C4-8", "packed"): 11882291,
 }
 
 
@@ -200,8 +200,12 @@ def main():
                 "note": "per entry of W (zeros included): 1 byte-to-float conversion + M fused multiply-adds; "
                         "peak = 256 CUs x 64 lanes x 2.4 GHz (one vector instruction per SIMD and 4 clocks)"}
     elif decode:
-        # small-M path streams the index arrays once (TCSC: four arrays; signed: one pointer array less): index-bandwidth bound
-        alg_bytes = 4 * nnz + 8 * (wl.N + 1) + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
+        # small-M path streams the index arrays once (TCSC: four arrays; signed: one pointer array less): index-bandwidth
+        # bound.  tstgemm() reads the padded 16-bit copy of the lists where the matrix has one and X fits the LDS whole
+        # (the library's rule: K <= 65535 and (K + 1) rows of M floats within 150 KiB).
+        narrow = args.variant == "tcsc" and lay.has_lists16 and wl.K <= 150 * 1024 // (4 * wl.M) - 1
+        list_bytes = 2 * (lay.nnz16_pos + lay.nnz16_neg) if narrow else 4 * nnz
+        alg_bytes = list_bytes + 8 * (wl.N + 1) + 4 * wl.M * wl.K + 4 * wl.M * wl.N + 4 * wl.N
         roof = {"bound": "hbm", "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "traffic": traffic}
     else:
@@ -217,6 +221,8 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["kernel"] = ("k_packed" if args.variant == "packed" else "k_decode (signed lists)" if args.variant == "signed"
                       else "k_decode" if decode else "k_small" if small else "k_large")
+    if decode and args.variant == "tcsc":
+        roof["kernel"] += " (16-bit lists)" if narrow else " (32-bit lists)"
     roof["kernel_ms"] = kernel_ms
     roof["kernel_ms_event_pair"] = kernel_raw_ms     # as read from the event pair ...
     roof["empty_event_pair_ms"] = pair_ms            # ... minus what an empty pair reads = kernel_ms
@@ -241,7 +247,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: M={wl.M} K={wl.K} N={wl.N} density={wl.density} X,b~{wl.dist} "
                                f"seed={wl.seed}", "nnz": nnz, "variant": args.variant, "matrix_copies_in_rotation": len(copies),
-                   "index_type": "int32 TCSC in; on device the TCSC arrays (M <= 64) or 64-bit row sets per K-block",
+                   "index_type": "int32 TCSC in; on device the TCSC arrays or their padded 16-bit copy (M <= 64), or 64-bit row sets "
+                                 "per K-block",
                    "tcsc_build_ms_host": build_ms, "upload_and_reblock_ms": upload_ms},
         "roofline": roof,
     }
