@@ -99,7 +99,7 @@ template <int NCW, int G>
 __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 {
     using geo = Geo<G>;
-    constexpr int L = geo::L, TM = geo::TM, RB = geo::RB;
+    constexpr int L = geo::L, RB = geo::RB;
     __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then the rows of the block
     char *const tile = lds + RB;
     const int M = a.M, N = a.N;
