@@ -203,7 +203,9 @@ int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, in
 
 /*
  * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront
- * (1, 2 or 4; the small-tile kernel has 1 and 2 and takes 4 as 2), number of K slices (1..8) computed by
+ * (1, 2, 4 or 8; the small-tile kernel has 1 and 2 and takes more as 2; 8 is the large-M path's shape for low
+ * densities, which never slices K and needs a padded column count that is a multiple of 128, else it runs as 4),
+ * number of K slices (1..8) computed by
  * different workgroups and summed in a fixed order (also the number of workgroups per column group of
  * tstgemm_packed()), and the largest number of row tiles of X packed and processed at a time (>= 1,
  * large-M path only).  0 restores the built-in choice for that parameter.  Process-wide.

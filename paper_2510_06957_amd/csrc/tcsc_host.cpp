@@ -330,7 +330,8 @@ int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, in
 
 int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)
 {
-    if (cols_per_wave != 0 && cols_per_wave != 1 && cols_per_wave != 2 && cols_per_wave != 4) return TSTGEMM_EINVAL;
+    if (cols_per_wave != 0 && cols_per_wave != 1 && cols_per_wave != 2 && cols_per_wave != 4 && cols_per_wave != 8)
+        return TSTGEMM_EINVAL;
     if (k_slices < 0 || k_slices > 8 || slab_tiles < 0) return TSTGEMM_EINVAL;
     tst::g_cols_per_wave = cols_per_wave;
     tst::g_k_slices = k_slices;

@@ -85,19 +85,27 @@ template <int R, int COUNT>
 __device__ __forceinline__ void read_rows(typename RowVec<R>::type (&v)[8], int lane_base, u64 &set)
 {
     int k, a;
-#define TST_OPERANDS \
-    : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a), [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), \
-      [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]) \
-    : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory"
+    // only the value registers a group of COUNT uses are operands, so that a smaller group holds fewer registers
+#define TST_TAIL : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory"
+#define TST_HEAD : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a), [v0] "=&v"(v[0]), [v1] "=&v"(v[1])
+#define TST_OPERANDS8 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]) TST_TAIL
+#define TST_OPERANDS6 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]) TST_TAIL
+#define TST_OPERANDS4 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]) TST_TAIL
+#define TST_OPERANDS2 TST_HEAD TST_TAIL
 #define TST_GROUP(w) \
-    if constexpr (COUNT == 8) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_READ2(6, 7, w) TST_OPERANDS); \
-    else if constexpr (COUNT == 6) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_OPERANDS); \
-    else if constexpr (COUNT == 4) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_OPERANDS); \
-    else asm volatile(TST_READ2(0, 1, w) TST_OPERANDS);
+    if constexpr (COUNT == 8) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_READ2(6, 7, w) TST_OPERANDS8); \
+    else if constexpr (COUNT == 6) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_OPERANDS6); \
+    else if constexpr (COUNT == 4) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_OPERANDS4); \
+    else asm volatile(TST_READ2(0, 1, w) TST_OPERANDS2);
     static_assert(COUNT == 8 || COUNT == 6 || COUNT == 4 || COUNT == 2, "group sizes");
     if constexpr (R == 4) { TST_GROUP("b128") } else if constexpr (R == 2) { TST_GROUP("b64") } else { TST_GROUP("b32") }
 #undef TST_GROUP
-#undef TST_OPERANDS
+#undef TST_OPERANDS8
+#undef TST_OPERANDS6
+#undef TST_OPERANDS4
+#undef TST_OPERANDS2
+#undef TST_HEAD
+#undef TST_TAIL
 }
 
 // acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it); when the set has
@@ -129,19 +137,23 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, int lane_b
 }
 
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
-// in groups of 8 and one last group of 6, 4 or 2 (7 or 8 left over: 8), i.e. with at most one gather of the row of
-// zeros per list.  The set is wave-uniform.
-template <int R, bool NEG>
+// in groups of GMAX = 8 and one last group of 6, 4 or 2 (7 or 8 left over: 8), i.e. with at most one gather of the row
+// of zeros per list.  GMAX = 4 (groups of 4 and a last one of 2): half the registers for values in flight, for the
+// launch shape with eight columns per wavefront, whose lists are short.  The set is wave-uniform.
+template <int R, bool NEG, int GMAX>
 __device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, int lane_base)
 {
+    static_assert(GMAX == 8 || GMAX == 4, "group sizes");
     int n = members(set);
-    while (n >= 7) {
-        gather<R, NEG, 8>(acc, lane_base, set);
-        n -= 8;
+    while (n >= GMAX - 1) {
+        gather<R, NEG, GMAX>(acc, lane_base, set);
+        n -= GMAX;
     }
-    // n is now in [-1, 6]; independent tests instead of an else-chain keep the accumulators in place
-    if (n >= 5) gather<R, NEG, 6>(acc, lane_base, set);
-    if (n == 3 || n == 4) gather<R, NEG, 4>(acc, lane_base, set);
+    // n is now in [-1, GMAX - 2]; independent tests instead of an else-chain keep the accumulators in place
+    if constexpr (GMAX == 8) {
+        if (n >= 5) gather<R, NEG, 6>(acc, lane_base, set);
+        if (n == 3 || n == 4) gather<R, NEG, 4>(acc, lane_base, set);
+    }
     if (n == 1 || n == 2) gather<R, NEG, 2>(acc, lane_base, set);
 }
 
@@ -158,8 +170,8 @@ struct LargeArgs {
     int alpha_stride;
 };
 
-// R rows per lane, NCW columns per wavefront.
-template <int R, int NCW>
+// R rows per lane, NCW columns per wavefront, gather groups of at most GMAX.
+template <int R, int NCW, int GMAX>
 __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
 {
     typedef typename RowVec<R>::type V;
@@ -225,8 +237,8 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         for (int kb = kb0; kb < kb1; ++kb) {
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
-                run_list<R, false>(acc[j], sets[2 * j], lane_base);
-                run_list<R, true>(acc[j], sets[2 * j + 1], lane_base);
+                run_list<R, false, GMAX>(acc[j], sets[2 * j], lane_base);
+                run_list<R, true, GMAX>(acc[j], sets[2 * j + 1], lane_base);
             }
             if (kb + 1 == kb1) break;
             // Exchange the tile.  The requests for the next K-block go out before the barrier, into the registers
@@ -258,19 +270,22 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     float bias[NCW];
 #pragma unroll
     for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
-    const bool store_vec = NCW == 4 && (N % 4 == 0) && (c0 + 4 <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
+    const bool store_vec = NCW % 4 == 0 && (N % 4 == 0) && (c0 + NCW <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int m = m0 + lane * R + r;
         if (m >= M) continue;
         float *yrow = a.Y + (size_t)m * N + c0;
-        if constexpr (NCW == 4) {
+        if constexpr (NCW % 4 == 0) {
             if (store_vec) {
-                float4v o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    o[j] = activate(lane_of<R>(acc[j], r) + bias[j], a.alpha, a.alpha_stride, c0 + j);
-                *reinterpret_cast<float4v *>(yrow) = o;
+                for (int j0 = 0; j0 < NCW; j0 += 4) {
+                    float4v o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        o[j] = activate(lane_of<R>(acc[j0 + j], r) + bias[j0 + j], a.alpha, a.alpha_stride, c0 + j0 + j);
+                    *reinterpret_cast<float4v *>(yrow + j0) = o;
+                }
                 continue;
             }
         }
@@ -281,7 +296,7 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
 }
 
 // One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles must fit the workspace.
-template <int R, int NCW>
+template <int R, int NCW, int GMAX = 8>
 hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int rows, int k_slices,
                   hipStream_t stream)
 {
@@ -300,6 +315,11 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     a.alpha = act.alpha; a.alpha_stride = act.alpha_stride;
     a.partials = d.partials;
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
+    if constexpr (NCW == 8) {
+        // 128 columns per workgroup: the reduction kernel has no tile of that width, so K is never sliced here
+        if (l.n_pad % (NW * NCW) != 0) return hipErrorInvalidValue;
+        k_slices = 1;
+    }
     a.n_colgroups = l.n_pad / (NW * NCW);
     const long long groups = m_tiles * a.n_colgroups;
     if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
@@ -312,7 +332,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_large<R, NCW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL((k_large<R, NCW, GMAX>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
     if (e != hipSuccess || k_slices == 1) return e;
@@ -321,14 +341,21 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
 
 // Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave
 // compute units idle, into as few slices as fill them.  X is processed in slabs of as many row tiles as the
-// workspace holds.
+// workspace holds.  With 8 columns per wavefront (128 per workgroup, gather groups of at most 4) a workgroup
+// exchanges its tile half as often per column; that shape is taken when the column count allows it, rows x columns
+// fill the chip without slicing K, and the estimate below says it is faster.  Measured on M = 4096, K = 4096,
+// N = 8192 (whole rounds of workgroups in both shapes), time in us against the density d: 3760 d + 520 with 4
+// columns, 3966 d + 316 with 8 -- 4 % faster at d = 0.5, 31 % at 1/16; the estimate scales these with the number of
+// rounds of workgroups each shape needs (a last round that is partly filled costs a whole one).
 template <int R>
 hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
     constexpr int TM = 64 * R;
-    const int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
+    const bool wide_fits = l.n_pad % (NW * 8) == 0;
+    const double density = (double)(l.nnz_pos + l.nnz_neg) / ((double)l.K * (double)l.N);
+    const double gain8 = (3760.0 * density + 520.0) / (3966.0 * density + 316.0);   // time of a 64-column pair / time of a 128-column workgroup
     const size_t tile_bytes = (size_t)l.n_kblocks * kKBlock * TM * sizeof(float);
     long long slab_rows = (long long)(d.xt_capacity / tile_bytes) * TM;
     if (slab_rows < TM) return hipErrorInvalidValue;
@@ -337,10 +364,17 @@ hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation 
     for (long long m_begin = 0; m_begin < M; m_begin += slab_rows) {
         const int rows = (int)((M - m_begin) < slab_rows ? (M - m_begin) : slab_rows);
         const long long m_tiles = (rows + TM - 1) / TM;
+        const int slots = 2 * compute_units();   // two workgroups per compute unit
+        int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
+        if (g_cols_per_wave == 0 && wide_fits) {
+            const long long groups8 = m_tiles * (l.n_pad / (NW * 8)), groups4 = 2 * groups8;
+            const long long rounds8 = (groups8 + slots - 1) / slots, rounds4 = (groups4 + slots - 1) / slots;
+            if (groups8 >= slots && 2.0 * (double)rounds8 <= (double)rounds4 * gain8) ncw = 8;
+        }
+        if (ncw == 8 && !wide_fits) ncw = 4;
         const long long groups = m_tiles * (l.n_pad / (NW * ncw));
         int k_slices = g_k_slices;
         if (k_slices == 0) {
-            const int slots = 2 * compute_units();   // two workgroups per compute unit
             k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
             if (k_slices > 8) k_slices = 8;
         }
@@ -351,6 +385,7 @@ hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation 
         switch (ncw) {
         case 1: e = launch<R, 1>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
         case 2: e = launch<R, 2>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
+        case 8: e = launch<R, 8, 4>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
         default: e = launch<R, 4>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
         }
         if (e != hipSuccess) return e;

@@ -147,11 +147,12 @@ def test_prefill_config_sampled_rows(name):
     assert np.array_equal(Yi[rows], Ydi.astype(np.float32))
 
 
-@pytest.mark.parametrize("cols_per_wave", [1, 2, 4])
+@pytest.mark.parametrize("cols_per_wave", [1, 2, 4, 8])
 @pytest.mark.parametrize("k_slices", [1, 3, 8])
 def test_launch_shapes(cols_per_wave, k_slices):
     """Every launch shape of the large-M path (columns per wavefront, K slices with the reduction kernel, X packed
-    and processed in slabs of one or two row tiles) gives the same, correct result; integer inputs bit for bit."""
+    and processed in slabs of one or two row tiles) gives the same, correct result; integer inputs bit for bit.
+    (Eight columns per wavefront never slice K: the request for slices is ignored there.)"""
     M, K, N = 600, 700, 200
     W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=41)
     _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=42)
@@ -168,6 +169,47 @@ def test_launch_shapes(cols_per_wave, k_slices):
             assert np.array_equal(Yi, Ydi.astype(np.float32))
     finally:
         tg.tstgemm_set_tuning(0, 0, 0)
+
+
+@pytest.mark.parametrize("M,K,N,density", [(100, 300, 256, 0.1), (700, 130, 384, 0.03), (300, 200, 200, 0.5),
+                                             (257, 64, 100, 0.06)])
+def test_eight_columns_per_wavefront(M, K, N, density):
+    """The launch shape for low densities (8 columns per wavefront, gather groups of at most 4), forced here on small
+    shapes: both tile heights, a column count that is and one that is not a multiple of 128 (the latter falls back to 4
+    columns), ragged N; against the oracle, integer inputs bit for bit."""
+    W, X, b = si.make_inputs(M, K, N, density, "normal", seed=4242 + M)
+    _, Xi, bi = si.make_inputs(M, K, N, density, "int8", seed=4243 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
+    try:
+        tg.tstgemm_set_tuning(8, 0, 0)
+        Y, h = gpu_tstgemm(W, X, b)
+        assert_close(Y, Yd, A, "8 columns per wavefront")
+        Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h)
+        assert np.array_equal(Yi, Ydi.astype(np.float32))
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+
+
+def test_low_density_tall_and_wide_picks_its_own_shape():
+    """Tall X, wide and sparse W: rows x columns fill the chip with 128-column workgroups, so the library takes the
+    low-density launch shape by itself.  Whole rows and scattered elements against the oracle; integer inputs exact."""
+    M, K, N = 4096, 200, 4096
+    W, X, b = si.make_inputs(M, K, N, 0.05, "uniform", seed=777)
+    ot = oracle.tcsc_build(W)
+    Y, h = gpu_tstgemm(W, X, b)
+    rows = np.array([0, 1, 255, 256, 2047, 4095], dtype=np.int32)
+    Yd, A, _ = oracle.tstgemm(X, ot, b, rows=rows)
+    assert_close(Y[rows], Yd, A, "rows")
+    rng = np.random.Generator(np.random.PCG64(9))
+    ms, ns = rng.integers(0, M, 4096), rng.integers(0, N, 4096)
+    Yp, Ap = oracle.tstgemm_points(X, ot, b, ms, ns)
+    assert_close(Y[ms, ns], Yp, Ap, "points")
+    Xi = si.draw_dense(np.random.Generator(np.random.PCG64(5)), X.shape, "int8")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, b, rows=rows)
+    assert np.array_equal(Yi[rows], Ydi.astype(np.float32))
 
 
 @pytest.mark.parametrize("cols_per_wave", [0, 1])
