@@ -346,6 +346,31 @@ def test_prelu_epilogue(M, K, N, per_column):
     assert_exact(Yi, Ypi, f"prelu integer {M}x{K}x{N}")
 
 
+@pytest.mark.parametrize("per_column", [False, True])
+def test_prelu_in_the_eight_column_shape(per_column):
+    """The fused PReLU in the output path of the large-M kernel's shape with 8 columns per wavefront (vector stores of
+    two pieces of four columns, and the single stores of a ragged last column group)."""
+    M, K, N = 300, 150, 380   # n_pad = 384 = 3 x 128
+    W, X, b = si.make_inputs(M, K, N, 0.2, "normal", seed=91)
+    rng = np.random.default_rng(92)
+    alpha = rng.uniform(-1.5, 2.5, N).astype(np.float32) if per_column else np.array([0.25], np.float32)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Yp, Ap = oracle.prelu(Yd, A, alpha)
+    _, Xi, bi = si.make_inputs(M, K, N, 0.2, "int8", seed=93)
+    a2 = (2.0 ** rng.integers(-3, 3, N)).astype(np.float32) if per_column else np.array([0.5], np.float32)
+    Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
+    Ypi, _ = oracle.prelu(Ydi, None, a2)
+    try:
+        tg.tstgemm_set_tuning(8, 0, 0)
+        Y, h = gpu_tstgemm(W, X, b, alpha=alpha)
+        assert_close(Y, Yp, Ap, "prelu, 8 columns per wavefront")
+        Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h, alpha=a2)
+        assert_exact(Yi, Ypi, "prelu integer, 8 columns per wavefront")
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+
+
 def test_prelu_rejects_bad_slopes():
     import torch
     W, X, b = si.make_inputs(4, 64, 8, 0.5, "normal", seed=64)
