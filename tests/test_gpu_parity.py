@@ -267,6 +267,23 @@ def test_very_tall_x():
     assert_close(Y3, Yd, A, f"{M}x{K}x{N} in slabs")
 
 
+def test_very_tall_x_wide_columns():
+    """Tall X against 256 columns: enough (row tile, 128-column group) pairs for the shape with 8 columns per
+    wavefront to be taken by itself; the same forced through slabs of three row tiles."""
+    M, K, N = 70000, 70, 256
+    W, X, b = si.make_inputs(M, K, N, 0.3, "normal", seed=96)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    try:
+        tg.tstgemm_set_tuning(8, 0, 3)
+        Y3, _ = gpu_tstgemm(W, X, b, handle=h)
+    finally:
+        tg.tstgemm_set_tuning(0, 0, 0)
+    assert_close(Y3, Yd, A, f"{M}x{K}x{N} in slabs, 8 columns per wavefront")
+
+
 @pytest.mark.parametrize("M", [3, 40, 130, 300])
 def test_very_long_k(M):
     """K = 100000 (1563 K-blocks, 391 list cuts, several LDS chunks of the decode kernel) with a handful of columns:
