@@ -203,8 +203,8 @@ int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, in
 
 /*
  * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront
- * (1, 2, 4 or 8; the small-tile kernel has 1 and 2 and takes more as 2; 8 is the large-M path's shape for low
- * densities, which never slices K and needs a padded column count that is a multiple of 128, else it runs as 4),
+ * (1, 2, 4 or 8; the small-tile kernel has 1, 2 and 4 and takes 8 as 4; 8 is the large-M path's wide
+ * shape, which never slices K and needs a padded column count that is a multiple of 128, else it runs as 4),
  * number of K slices (1..8) computed by
  * different workgroups and summed in a fixed order (also the number of workgroups per column group of
  * tstgemm_packed()), and the largest number of row tiles of X packed and processed at a time (>= 1,

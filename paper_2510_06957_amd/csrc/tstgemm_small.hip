@@ -160,10 +160,15 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
                 int4v qn = first_step(a.rin, lo[2 * j + 1]);
-                run_slice<G, false>(acc[j], q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
+                // The column's sums are a value of their own while its lists are walked and the array is only touched
+                // here: updated in place inside the loops, the whole array went through copies (and, with four
+                // columns, spills) at every step.
+                float4v sum = acc[j];
+                run_slice<G, false>(sum, q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
                 // behind the last column: the first slice of the next block starts where this block's ended
                 q = first_step(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
-                run_slice<G, true>(acc[j], qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
+                run_slice<G, true>(sum, qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
+                acc[j] = sum;
             }
 #pragma unroll
             for (int i = 0; i < 2 * NCW; ++i) lo[i] = hi[i];
@@ -254,29 +259,41 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
 
 }  // namespace
 
-// M <= 64: one tile of 64 rows, or of 32 / 16 rows with two / four times as many rows of W per block.  Two columns per wavefront and
-// K sliced (at block borders) as far as it takes to give every compute unit two workgroups; a short K (at most four
-// list cuts) is not sliced and takes one column per wavefront instead, which saves the reduction kernel.
+// M <= 64: one tile of 64 rows, or of 32 / 16 rows with two / four times as many rows of W per block.  K is sliced (at
+// block borders) as far as it takes to give every compute unit two workgroups.  Columns per wavefront: 4 (64 per
+// workgroup: a block of the tile in the LDS serves twice the columns, half the exchanges per column) when that still
+// fills the chip with at most 8 slices of at least 4 blocks each; else 2; a short K (at most four list cuts) is not
+// sliced and takes one column per wavefront, which saves the reduction kernel.
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
                         hipStream_t stream)
 {
     if (M > 64) return hipErrorInvalidValue;
     const tcsc_layout_t &l = t->layout;
     const bool short_k = l.n_cuts <= 4;
-    const int ncw = g_cols_per_wave ? (g_cols_per_wave == 1 ? 1 : 2) : (short_k ? 1 : 2);
+    const int G = M <= 16 ? 16 : M <= 32 ? 8 : 4;
+    const int slots = 2 * compute_units();
+    int ncw = g_cols_per_wave ? (g_cols_per_wave == 1 ? 1 : g_cols_per_wave == 2 ? 2 : 4) : (short_k ? 1 : 2);
+    if (g_cols_per_wave == 0 && !short_k) {
+        const int block_rows = STAGE / (4 * (256 / G));            // rows of W per block of the tile
+        const long long n_blocks = (l.K + block_rows - 1) / block_rows;
+        const long long groups4 = l.n_pad / (NW * 4);
+        const long long slices4 = groups4 >= slots ? 1 : (slots + groups4 - 1) / groups4;
+        if (slices4 <= kMaxKSlices && n_blocks >= 4 * slices4) ncw = 4;
+    }
     const long long groups = l.n_pad / (NW * ncw);
     int k_slices = g_k_slices;
-    if (k_slices == 0) {
-        const int slots = 2 * compute_units();
-        k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
+    if (k_slices == 0) k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
+    switch (G * 8 + ncw) {
+    case 16 * 8 + 1: return launch<1, 16>(X, t, b, act, Y, M, k_slices, stream);
+    case 16 * 8 + 2: return launch<2, 16>(X, t, b, act, Y, M, k_slices, stream);
+    case 16 * 8 + 4: return launch<4, 16>(X, t, b, act, Y, M, k_slices, stream);
+    case 8 * 8 + 1: return launch<1, 8>(X, t, b, act, Y, M, k_slices, stream);
+    case 8 * 8 + 2: return launch<2, 8>(X, t, b, act, Y, M, k_slices, stream);
+    case 8 * 8 + 4: return launch<4, 8>(X, t, b, act, Y, M, k_slices, stream);
+    case 4 * 8 + 1: return launch<1, 4>(X, t, b, act, Y, M, k_slices, stream);
+    case 4 * 8 + 2: return launch<2, 4>(X, t, b, act, Y, M, k_slices, stream);
+    default: return launch<4, 4>(X, t, b, act, Y, M, k_slices, stream);
     }
-    if (M <= 16)
-        return ncw == 1 ? launch<1, 16>(X, t, b, act, Y, M, k_slices, stream)
-                        : launch<2, 16>(X, t, b, act, Y, M, k_slices, stream);
-    if (M <= 32)
-        return ncw == 1 ? launch<1, 8>(X, t, b, act, Y, M, k_slices, stream)
-                        : launch<2, 8>(X, t, b, act, Y, M, k_slices, stream);
-    return ncw == 1 ? launch<1, 4>(X, t, b, act, Y, M, k_slices, stream) : launch<2, 4>(X, t, b, act, Y, M, k_slices, stream);
 }
 
 }  // namespace tst

@@ -212,7 +212,7 @@ def test_low_density_tall_and_wide_picks_its_own_shape():
     assert np.array_equal(Yi[rows], Ydi.astype(np.float32))
 
 
-@pytest.mark.parametrize("cols_per_wave", [0, 1])
+@pytest.mark.parametrize("cols_per_wave", [0, 1, 4])
 @pytest.mark.parametrize("k_slices", [0, 1, 3, 8])
 @pytest.mark.parametrize("M,K,N,density", [(64, 1100, 200, 0.5), (33, 257, 70, 0.5), (9, 2100, 40, 0.0625),
                                            (50, 600, 130, 1.0), (16, 256, 64, 0.25), (32, 1100, 100, 0.5),
