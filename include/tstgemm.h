@@ -231,6 +231,22 @@ int tstgemm_set_decode_lists(int wide);
  */
 int tstgemm_profile_events(void *before, void *after);
 
+/*
+ * Measurement probes (not part of the product path): what the machine delivers on the two resources the
+ * kernels are priced against (operational intensity and peak, Sec. 4), for a benchmark that wants the
+ * measured rate beside the datasheet one.  Both only enqueue one kernel on `stream`; the caller times it.
+ *
+ * tstgemm_probe_lds_read: 2 workgroups of 16 wavefronts per compute unit (the large-M kernel's occupancy), every
+ * wavefront issues 8 * iters conflict-free 16-byte-per-lane LDS reads and nothing else.  *bytes_read (HOST,
+ * may be NULL) receives the bytes all wavefronts read together.  1 <= iters <= 2^20, else EINVAL.
+ *
+ * tstgemm_probe_stream_read: reads buf (DEVICE, 16-byte aligned, bytes >= 16; whole 16-byte pieces are read,
+ * a tail of bytes % 16 is not) once with 16-byte loads, grid-stride, 8 workgroups of 256 threads per
+ * compute unit.  Errors: EINVAL, EHIP.
+ */
+int tstgemm_probe_lds_read(int iters, int64_t *bytes_read, void *stream);
+int tstgemm_probe_stream_read(const void *buf, size_t bytes, void *stream);
+
 /* Release the handle and its host arrays (not the device buffer).  NULL is allowed. */
 void tcsc_destroy(tcsc_t *t);
 

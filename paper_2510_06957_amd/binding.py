@@ -78,6 +78,10 @@ def _load():
     lib.tstgemm_set_decode_lists.restype = ci
     lib.tstgemm_profile_events.argtypes = [vp, vp]
     lib.tstgemm_profile_events.restype = ci
+    lib.tstgemm_probe_lds_read.argtypes = [ci, ctypes.POINTER(ctypes.c_int64), vp]
+    lib.tstgemm_probe_lds_read.restype = ci
+    lib.tstgemm_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp]
+    lib.tstgemm_probe_stream_read.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_signed", "tstgemm_packed",
                  "tcsc_signed_arrays", "tcsc_packed_codes"):
@@ -301,6 +305,20 @@ def tstgemm_profile_events(before=None, after=None):
     native handles exist), or None for both to switch the recording off."""
     raw = [None if e is None else ctypes.c_void_p(e.cuda_event) for e in (before, after)]
     _check(_load().tstgemm_profile_events(*raw), "tstgemm_profile_events")
+
+
+def tstgemm_probe_lds_read(iters: int, stream=None) -> int:
+    """Enqueue the LDS-read probe kernel; returns the bytes its wavefronts read together."""
+    n = ctypes.c_int64()
+    _check(_load().tstgemm_probe_lds_read(int(iters), ctypes.byref(n), _stream_ptr(stream)), "tstgemm_probe_lds_read")
+    return n.value
+
+
+def tstgemm_probe_stream_read(buf, stream=None) -> int:
+    """Enqueue the streaming-read probe kernel over a CUDA tensor; returns the bytes it reads."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(_load().tstgemm_probe_stream_read(buf.data_ptr(), nbytes, _stream_ptr(stream)), "tstgemm_probe_stream_read")
+    return nbytes // 16 * 16
 
 
 def tcsc_destroy(t: Tcsc):

@@ -159,9 +159,15 @@ def test_bench_refuses_more_than_one_gpu(argv, env):
 
 
 def test_bench_traffic_table_names_real_workloads():
+    """Every entry of bench.py's table of counter-measured HBM traffic names a real workload and a tracked summary."""
     tree = ast.parse((ROOT / "bench.py").read_text())
-    table = next(n for n in ast.walk(tree) if isinstance(n, ast.Assign) and getattr(n.targets[0], "id", "") == "MEASURED_TRAFFIC")
-    keys = ast.literal_eval(table.value)
-    for (name, variant), value in keys.items():
+    consts = {n.targets[0].id: ast.literal_eval(n.value) for n in tree.body
+              if isinstance(n, ast.Assign) and isinstance(n.value, ast.Constant) and isinstance(n.value.value, str)}
+    table = next(n for n in tree.body if isinstance(n, ast.Assign) and getattr(n.targets[0], "id", "") == "MEASURED_TRAFFIC")
+    for key, value in zip(table.value.keys, table.value.values):
+        name, variant = ast.literal_eval(key)
+        nbytes, source = value.elts
+        source = consts[source.id] if isinstance(source, ast.Name) else ast.literal_eval(source)
         si.workload(name)
-        assert variant in ("tcsc", "signed", "packed") and value > 0
+        assert variant in ("tcsc", "signed", "packed") and ast.literal_eval(nbytes) > 0
+        assert (ROOT / source).is_file(), source
