@@ -220,10 +220,10 @@ def main():
     copies = [t] + [tg.tcsc_upload(tg.tcsc_build(W)) for _ in range(n_copies - 1)]
     turn = [0]
 
-    def gemm_next():
+    def gemm_next(**options):
         h = copies[turn[0] % len(copies)]
         turn[0] += 1
-        gemm(Xd, h, bd, Yd, stream)
+        gemm(Xd, h, bd, Yd, stream, **options)
 
     if args.traffic_calibration:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")   # 256 MiB read, 256 MiB written per copy
@@ -280,18 +280,16 @@ def main():
         torch.cuda.synchronize()
         warm_ms = e0.elapsed_time(e1) / steps
 
-    # The dominant kernel alone: the library records a pair of HIP events around its launch, on the launch stream,
-    # in every call of a second, equally long run (back to back as before, so the clocks stay up).
+    # The dominant kernel alone: the library records a pair of HIP events (an option of the call) around its launch, on the
+    # launch stream, in every call of a second, equally long run (back to back as before, so the clocks stay up).
     n_k = max(min(steps, 1000), 20)
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_k)]
     for a, c in pairs:
         a.record(stream)
         c.record(stream)
     torch.cuda.synchronize()
-    for a, c in pairs:
-        tg.tstgemm_profile_events(a, c)
-        gemm_next()
-    tg.tstgemm_profile_events(None, None)
+    for pair in pairs:
+        gemm_next(events=pair)
     torch.cuda.synchronize()
     kernel_raw = np.array([a.elapsed_time(c) for a, c in pairs])
     # What an event pair reads with nothing between its two records, on the same busy stream: the cost of the

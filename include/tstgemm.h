@@ -4,9 +4,9 @@
  * C ABI of libtstgemm.so.  Plain pointers and sizes only; every pointer argument says
  * whether it is HOST or DEVICE memory.  All functions return 0 (TSTGEMM_OK) or a negative
  * TSTGEMM_E* code; tcsc_strerror() turns a code into text.  No function throws, aborts or
- * prints.  Besides what a handle owns the library keeps three pieces of global state: the tuning
- * overrides of tstgemm_set_tuning(), the choice of tstgemm_set_decode_lists() and the event pair of
- * tstgemm_profile_events().
+ * prints.  The library keeps no mutable global state: everything a call depends on is in its
+ * arguments and in the handle (what the library caches per device -- the number of compute units, a
+ * kernel attribute that has been set -- is read-only information about the machine).
  *
  * The operation is Eq. 1 of the paper (Sec. 2): X is dense fp32 (M x K, row-major), W is a
  * K x N matrix with entries in {-1, 0, +1}, b (N) is added to every row of the product,
@@ -34,7 +34,11 @@ extern "C" {
 #define TSTGEMM_ENOTUPLOADED (-3) /* tstgemm() on a handle that tcsc_upload() has not filled */
 #define TSTGEMM_EHIP (-4)         /* a HIP runtime call failed (launch, copy) */
 #define TSTGEMM_ENOMEM (-5)       /* host allocation failed, or the device buffer passed in is too small */
-#define TSTGEMM_ETOOBIG (-6)      /* more than 2^31-1 entries in one sign list, or K >= 2^31 */
+#define TSTGEMM_ETOOBIG (-6)      /* more than 2^31-1 non-zero entries (both signs together), or K >= 2^31 */
+#define TSTGEMM_ENOFORM (-7)      /* the device form this call reads was not selected for the upload
+                                     (tcsc_select_forms) */
+#define TSTGEMM_EWORKSPACE (-8)   /* the call needs scratch memory and has none (no workspace argument and none in
+                                     the handle), or less than tstgemm_workspace_bytes() gives as the minimum */
 
 /* Opaque handle: owns a host copy of the four TCSC arrays; after tcsc_upload() it also
  * remembers (borrows, never frees) the caller's device buffer holding the device form. */
@@ -104,10 +108,12 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *                                             of column n is byte [g / 16][n][g % 16], groups beyond ceil(K/5) and
  *                                             columns >= N hold code 0.  n_chunks5 = ceil(ceil(K/5) / 16).
  *                                             Read by tstgemm_packed().
- *   workspace  bytes  [workspace_bytes]       scratch of tstgemm(): split-K partial sums (32 MiB) and a tiled,
- *                                             transposed copy of (a slab of rows of) X (128 MiB, or one tile of
- *                                             256 rows over the padded K if that is larger)
+ *   workspace  bytes  [workspace_bytes]       scratch for calls that bring none of their own: split-K partial sums and
+ *                                             a tiled, transposed copy of (a slab of rows of) X; 160 MiB, or 32 MiB + one
+ *                                             tile of 256 rows over the padded K if that is larger
  * n_pad = N rounded up to a multiple of 64; columns >= N have empty sets.
+ * Which of these the buffer holds is the handle's choice of forms (tcsc_select_forms; default: all); a form
+ * that is not selected has offset 0 and takes no room.  The four TCSC arrays are always there.
  */
 typedef struct tcsc_layout {
     int32_t K, N, n_pad, k_block, n_kblocks, n_cuts;   /* n_cuts = K / 256 rounded up */
@@ -118,7 +124,29 @@ typedef struct tcsc_layout {
     size_t off_masks, off_list_cuts;
     size_t off_col_start16_pos, off_col_start16_neg, off_row_index16_pos, off_row_index16_neg;
     size_t off_signed_index, off_packed, off_workspace, workspace_bytes, total_bytes;
+    uint32_t forms;                 /* TCSC_FORM_* bits of what the buffer holds */
 } tcsc_layout_t;
+
+/*
+ * Device forms besides the four TCSC arrays (which are always uploaded: the decode kernel of tstgemm() for
+ * M <= 8 reads them, and every other form is derived from them on the GPU):
+ */
+#define TCSC_FORM_ROWSETS 1u     /* masks: the large-M path of tstgemm(), M > 64 */
+#define TCSC_FORM_CUTS 2u        /* list_cuts: the small-tile path of tstgemm(), 8 < M <= 64 */
+#define TCSC_FORM_LISTS16 4u     /* padded 16-bit lists (only where K <= 65535): M <= 8 reads half the bytes */
+#define TCSC_FORM_SIGNED 8u      /* signed_index: tstgemm_signed() */
+#define TCSC_FORM_PACKED 16u     /* packed: tstgemm_packed(); built from the row sets, so it selects ROWSETS too */
+#define TCSC_FORM_WORKSPACE 32u  /* scratch inside the buffer, for calls without a workspace argument */
+#define TCSC_FORM_ALL 63u
+
+/*
+ * Choose what tcsc_upload() puts into the device buffer (a new handle has TCSC_FORM_ALL).  Changes
+ * tcsc_device_bytes() and tcsc_layout(); a handle that was already uploaded must be uploaded again.  A matrix that
+ * serves one shape of X needs one form: e.g. ROWSETS alone for M > 64 with a caller-supplied workspace
+ * (tstgemm_ex) is 16 bytes per column and 64 rows of W beside the TCSC arrays.
+ * Errors: EINVAL for a NULL handle or bits outside TCSC_FORM_ALL.
+ */
+int tcsc_select_forms(tcsc_t *t, uint32_t forms);
 
 int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out);
 
@@ -144,14 +172,63 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * X, lists read from the TCSC arrays between the list cuts), everything else the large-M path (row sets).
  * Asynchronous: the kernels are enqueued on `stream` (a hipStream_t, NULL = null stream), no host
  * synchronisation, no allocation.
- * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, EHIP (launch failure).
- * Rounding: fp32 accumulation in an order fixed by (M, K, N), the matrix and the tuning
- * parameters; repeated calls give bit-identical results.  Integer-valued inputs small enough
+ * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, ENOFORM, EWORKSPACE, EHIP (launch failure).
+ * Rounding: fp32 accumulation in an order fixed by (M, K, N), the matrix, the launch-shape options and the
+ * size of the workspace; repeated calls give bit-identical results.  Integer-valued inputs small enough
  * for fp32 give exact results.
- * Two calls that use the same handle must be ordered (same stream, or an event between them):
- * they share the handle's workspace.
+ * Scratch memory (M > 8): this call uses the workspace inside the handle's device buffer (TCSC_FORM_WORKSPACE),
+ * so two calls on the same handle must be ordered (same stream, or an event between them).  tstgemm_ex() takes
+ * a workspace argument instead.
  */
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
+
+/*
+ * Scratch memory a call with these dimensions needs (the tiled, transposed copy of X of the paths for M > 8 and
+ * the partial sums of K slices; Sec. 3 "Blocking" is where the tiles come from).  *min_bytes: the least a call
+ * runs with (one row tile of X over the padded K; rows then go through in slabs and K is not sliced);
+ * *best_bytes: what it takes to run every shape the library would choose by itself in one slab.  M <= 8: 0
+ * and the (small) partial sums tstgemm_packed() may use.  Either pointer may be NULL.  Errors: EINVAL.
+ */
+int tstgemm_workspace_bytes(int M, int K, int N, size_t *min_bytes, size_t *best_bytes);
+
+/*
+ * Everything a call can be told beyond its operands.  Zero-initialise, set struct_size = sizeof(tstgemm_opts_t)
+ * and the fields that matter; a zeroed struct (with struct_size) makes tstgemm_ex() the same as tstgemm().
+ */
+typedef struct tstgemm_opts {
+    size_t struct_size;
+    int encoding;            /* 0: TCSC (as tstgemm), 1: inverted index (as tstgemm_signed, M <= 8),
+                                2: value compression (as tstgemm_packed, M <= 8, X finite) */
+    int alpha_count;         /* 1 or N when alpha is given */
+    const float *alpha;      /* DEVICE PReLU slopes (as tstgemm_prelu; encoding 0 only) or NULL for none */
+    void *workspace;         /* DEVICE scratch, 256-byte aligned, owned by the caller, or NULL for the handle's own.
+                                Used from the moment the call is enqueued until its last kernel has finished; calls
+                                whose kernels may overlap (different streams) need different workspaces, calls on one
+                                stream can share one across any number of matrices */
+    size_t workspace_bytes;  /* at least the min_bytes of tstgemm_workspace_bytes(), else EWORKSPACE */
+    /* Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests; 0 = the built-in choice.
+     * cols_per_wave: 1, 2, 4 or 8 columns of Y per wavefront (the small-tile kernel has 1, 2, 4 and takes 8 as 4; 8 is
+     * the large-M path's wide shape, which needs a padded column count that is a multiple of 128, else it runs as 4);
+     * k_slices: 1..8 slices of K computed by different workgroups and summed in slice order (also the workgroups per
+     * column group of encoding 2); slab_tiles: at most this many row tiles of X packed and processed at a time. */
+    int cols_per_wave, k_slices, slab_tiles;
+    int decode_wide_lists;   /* != 0: M <= 8 reads the 32-bit TCSC lists even where the padded 16-bit copy exists.  The two
+                                deal the entries of a list to the lanes differently, so fp32 rounding can differ in the
+                                last bits; integer-valued inputs give the same, exact result */
+    void *event_before, *event_after;   /* hipEvent_t pair (both or neither), recorded on the call's stream right before
+                                and after the launch of the main (gather-add) kernel, not around the packing
+                                pre-pass and the reduction of K slices; a call with several slabs of rows records
+                                them once per slab, so the pair then brackets the last slab.  The caller's. */
+} tstgemm_opts_t;
+
+/*
+ * Y = X W + b (Eq. 1) with options: tstgemm(), tstgemm_prelu(), tstgemm_signed() and tstgemm_packed() are this call
+ * with the options they stand for.  opts may be NULL (= tstgemm()).  Operands, rounding and asynchrony as for
+ * tstgemm().  Errors: as tstgemm(); EINVAL also for a struct_size that is not this header's, an unknown encoding,
+ * an option outside its range, exactly one event, alpha with encoding != 0, or a misaligned workspace.
+ */
+int tstgemm_ex(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N,
+               const tstgemm_opts_t *opts, void *stream);
 
 /*
  * Y = PReLU(X W + b): tstgemm() with the activation fused behind the bias add.  The paper fuses
@@ -195,41 +272,11 @@ int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, in
  * through a 243-entry table (as in the paper) into five weights, and ALL entries take part in the sum,
  * the zeros as x * 0.  Unlike every other entry point this one therefore reads X entries whose weight is
  * zero: X must be finite.  Products with -1, 0, +1 are exact, so the rounding is that of the additions,
- * in an order fixed by (M, K, N) and the tuning parameters.  Arguments otherwise as for tstgemm() (it may
+ * in an order fixed by (M, K, N) and the options.  Arguments otherwise as for tstgemm() (it may
  * use the handle's workspace, so calls on one handle must be ordered).  Errors: as tstgemm(), and EINVAL
  * for M > 8.
  */
 int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
-
-/*
- * Launch-shape overrides for the tiled paths (M > 8), for tuning runs and tests: columns per wavefront
- * (1, 2, 4 or 8; the small-tile kernel has 1, 2 and 4 and takes 8 as 4; 8 is the large-M path's wide
- * shape, which never slices K and needs a padded column count that is a multiple of 128, else it runs as 4),
- * number of K slices (1..8) computed by
- * different workgroups and summed in a fixed order (also the number of workgroups per column group of
- * tstgemm_packed()), and the largest number of row tiles of X packed and processed at a time (>= 1,
- * large-M path only).  0 restores the built-in choice for that parameter.  Process-wide.
- * Errors: EINVAL for a value outside the ranges above.
- */
-int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles);
-
-/*
- * Which copy of the lists the small-M kernel of tstgemm() reads when the matrix has both (K <= 65535): 0 (the
- * default) = the padded 16-bit copy, non-zero = the 32-bit TCSC arrays themselves.  For measurements and tests.  The
- * two deal the entries of a list to the lanes differently (8 or 4 consecutive ones per lane), so the fp32 rounding can
- * differ in the last bits; integer-valued inputs give the same, exact result.  Process-wide.  Always returns TSTGEMM_OK.
- */
-int tstgemm_set_decode_lists(int wide);
-
-/*
- * For benchmarks that must time one kernel: from now on every tstgemm() call records the
- * hipEvent_t `before` right before and `after` right after the launch of its main kernel
- * (the gather-add kernel; not the packing pre-pass and the split-K reduction of the tiled
- * paths), on the call's stream.  Both NULL switches this off (the default).  The events are
- * the caller's; a call with more than one slab of rows records them once per slab, so the pair
- * then brackets the last slab only.  Process-wide.  Errors: EINVAL if exactly one is NULL.
- */
-int tstgemm_profile_events(void *before, void *after);
 
 /*
  * Measurement probes (not part of the product path): what the machine delivers on the two resources the

@@ -33,7 +33,19 @@ class TcscLayout(ctypes.Structure):
                 ("off_col_start16_pos", ctypes.c_size_t), ("off_col_start16_neg", ctypes.c_size_t),
                 ("off_row_index16_pos", ctypes.c_size_t), ("off_row_index16_neg", ctypes.c_size_t),
                 ("off_signed_index", ctypes.c_size_t), ("off_packed", ctypes.c_size_t), ("off_workspace", ctypes.c_size_t),
-                ("workspace_bytes", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
+                ("workspace_bytes", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t), ("forms", ctypes.c_uint32)]
+
+
+class TstgemmOpts(ctypes.Structure):
+    """tstgemm_opts_t of include/tstgemm.h."""
+    _fields_ = [("struct_size", ctypes.c_size_t), ("encoding", ctypes.c_int), ("alpha_count", ctypes.c_int),
+                ("alpha", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("cols_per_wave", ctypes.c_int), ("k_slices", ctypes.c_int), ("slab_tiles", ctypes.c_int),
+                ("decode_wide_lists", ctypes.c_int), ("event_before", ctypes.c_void_p), ("event_after", ctypes.c_void_p)]
+
+
+# TCSC_FORM_* of include/tstgemm.h
+FORM_ROWSETS, FORM_CUTS, FORM_LISTS16, FORM_SIGNED, FORM_PACKED, FORM_WORKSPACE, FORM_ALL = 1, 2, 4, 8, 16, 32, 63
 
 
 def library_path() -> pathlib.Path:
@@ -72,19 +84,16 @@ def _load():
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
     lib.tcsc_strerror.restype = ctypes.c_char_p
-    lib.tstgemm_set_tuning.argtypes = [ci, ci, ci]
-    lib.tstgemm_set_tuning.restype = ci
-    lib.tstgemm_set_decode_lists.argtypes = [ci]
-    lib.tstgemm_set_decode_lists.restype = ci
-    lib.tstgemm_profile_events.argtypes = [vp, vp]
-    lib.tstgemm_profile_events.restype = ci
+    lib.tstgemm_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ctypes.POINTER(TstgemmOpts), vp]
+    lib.tstgemm_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+    lib.tcsc_select_forms.argtypes = [vp, ctypes.c_uint32]
     lib.tstgemm_probe_lds_read.argtypes = [ci, ctypes.POINTER(ctypes.c_int64), vp]
     lib.tstgemm_probe_lds_read.restype = ci
     lib.tstgemm_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp]
     lib.tstgemm_probe_stream_read.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_signed", "tstgemm_packed",
-                 "tcsc_signed_arrays", "tcsc_packed_codes"):
+                 "tcsc_signed_arrays", "tcsc_packed_codes", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -197,10 +206,26 @@ def _stream_ptr(stream):
     return s.cuda_stream
 
 
-def tcsc_upload(t: Tcsc, device="cuda:0", stream=None) -> Tcsc:
-    """Allocate the device buffer with torch and run the upload + GPU re-blocking pass into it."""
+def tcsc_select_forms(t: Tcsc, forms: int):
+    """Which device forms the next tcsc_upload() builds (FORM_* bits; a new handle has FORM_ALL)."""
+    _check(_load().tcsc_select_forms(t.handle, int(forms)), "tcsc_select_forms")
+
+
+def tstgemm_workspace_bytes(M: int, K: int, N: int):
+    """(min_bytes, best_bytes) of scratch memory for a call with these dimensions."""
+    lo, hi = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(_load().tstgemm_workspace_bytes(int(M), int(K), int(N), ctypes.byref(lo), ctypes.byref(hi)),
+           "tstgemm_workspace_bytes")
+    return lo.value, hi.value
+
+
+def tcsc_upload(t: Tcsc, device="cuda:0", stream=None, forms=None) -> Tcsc:
+    """Allocate the device buffer with torch and run the upload + GPU re-blocking pass into it.  forms: FORM_* bits
+    to select first (None: leave the handle's choice, all forms for a new handle)."""
     import torch
     dev = torch.device(device)
+    if forms is not None:
+        tcsc_select_forms(t, forms)
     with torch.cuda.device(dev):
         buf = torch.empty(tcsc_device_bytes(t) + 256, dtype=torch.uint8, device=dev)
         base = (buf.data_ptr() + 255) // 256 * 256
@@ -236,44 +261,76 @@ def _gemm_args(X, t: Tcsc, b, Y):
     return M, K, N, b_ptr, Y
 
 
-def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None):
+def _opts(X, N, encoding=0, alpha=None, workspace=None, cols_per_wave=0, k_slices=0, slab_tiles=0, wide_lists=False,
+          events=None):
+    """tstgemm_opts_t from keyword arguments, or None when every one has its default (argument marshalling only).
+    workspace: a CUDA tensor on X's device; events: a pair of torch.cuda.Event(enable_timing=True) objects that have
+    been recorded once (so that their native handles exist)."""
+    import torch
+    if (encoding == 0 and alpha is None and workspace is None and not cols_per_wave and not k_slices and not slab_tiles
+            and not wide_lists and events is None):
+        return None
+    o = TstgemmOpts()
+    o.struct_size = ctypes.sizeof(TstgemmOpts)
+    o.encoding = encoding
+    if alpha is not None:
+        if not (alpha.is_cuda and alpha.dtype == torch.float32 and alpha.is_contiguous() and alpha.numel() in (1, N)
+                and alpha.device.index == X.device.index):
+            raise ValueError("alpha must be a contiguous float32 CUDA tensor with 1 or N entries on X's device")
+        o.alpha, o.alpha_count = alpha.data_ptr(), alpha.numel()
+    if workspace is not None:
+        if not (workspace.is_cuda and workspace.is_contiguous() and workspace.device.index == X.device.index):
+            raise ValueError("workspace must be a contiguous CUDA tensor on X's device")
+        o.workspace, o.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    o.cols_per_wave, o.k_slices, o.slab_tiles = int(cols_per_wave), int(k_slices), int(slab_tiles)
+    o.decode_wide_lists = int(bool(wide_lists))
+    if events is not None:
+        o.event_before, o.event_after = events[0].cuda_event, events[1].cuda_event
+    return o
+
+
+def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None, **options):
     """Y = X W + b on the GPU, or Y = PReLU(X W + b) when `alpha` is given (tstgemm_prelu of the C ABI).
     X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None; alpha: cuda float32 with 1 or N entries.
+    options (tstgemm_ex of the C ABI): workspace=, cols_per_wave=, k_slices=, slab_tiles=, wide_lists=, events=.
 
     Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
     handle was uploaded to and the one holding X, b, alpha and Y."""
-    import torch
     M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
-    if alpha is not None and not (alpha.is_cuda and alpha.dtype == torch.float32 and alpha.is_contiguous()
-                                  and alpha.numel() in (1, N) and alpha.device.index == X.device.index):
-        raise ValueError("alpha must be a contiguous float32 CUDA tensor with 1 or N entries on X's device")
-    if alpha is None:
+    o = _opts(X, N, 0, alpha, **options)
+    if o is None:
         rc = _load().tstgemm(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
-    else:
-        rc = _load().tstgemm_prelu(X.data_ptr(), t.handle, b_ptr, alpha.data_ptr(), alpha.numel(), Y.data_ptr(), M, K, N,
+    elif not options:
+        rc = _load().tstgemm_prelu(X.data_ptr(), t.handle, b_ptr, o.alpha, o.alpha_count, Y.data_ptr(), M, K, N,
                                    _stream_ptr(stream))
+    else:
+        rc = _load().tstgemm_ex(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, ctypes.byref(o), _stream_ptr(stream))
     if rc != 0:
         raise TstgemmError(rc, "tstgemm")
     return Y
 
 
-def tstgemm_signed(X, t: Tcsc, b=None, Y=None, stream=None):
-    """Y = X W + b for M <= 8 from the inverted-index form of the uploaded matrix (tstgemm_signed of the C ABI)."""
+def _variant(name, encoding, X, t, b, Y, stream, options):
     M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
-    rc = _load().tstgemm_signed(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if options:
+        o = _opts(X, N, encoding, None, **options)
+        rc = _load().tstgemm_ex(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, ctypes.byref(o), _stream_ptr(stream))
+    else:
+        rc = getattr(_load(), name)(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
     if rc != 0:
-        raise TstgemmError(rc, "tstgemm_signed")
+        raise TstgemmError(rc, name)
     return Y
 
 
-def tstgemm_packed(X, t: Tcsc, b=None, Y=None, stream=None):
+def tstgemm_signed(X, t: Tcsc, b=None, Y=None, stream=None, **options):
+    """Y = X W + b for M <= 8 from the inverted-index form of the uploaded matrix (tstgemm_signed of the C ABI)."""
+    return _variant("tstgemm_signed", 1, X, t, b, Y, stream, options)
+
+
+def tstgemm_packed(X, t: Tcsc, b=None, Y=None, stream=None, **options):
     """Y = X W + b for M <= 8 from the value-compression form of the uploaded matrix (tstgemm_packed of the C ABI);
     X must be finite."""
-    M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
-    rc = _load().tstgemm_packed(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
-    if rc != 0:
-        raise TstgemmError(rc, "tstgemm_packed")
-    return Y
+    return _variant("tstgemm_packed", 2, X, t, b, Y, stream, options)
 
 
 def tcsc_signed_arrays(t: Tcsc):
@@ -289,22 +346,6 @@ def tcsc_packed_codes(t: Tcsc) -> np.ndarray:
     codes = np.empty((t.N, (t.K + 4) // 5), np.uint8)
     _check(_load().tcsc_packed_codes(t.handle, _np_ptr(codes)), "tcsc_packed_codes")
     return codes
-
-
-def tstgemm_set_tuning(cols_per_wave: int = 0, k_slices: int = 0, slab_tiles: int = 0):
-    _check(_load().tstgemm_set_tuning(int(cols_per_wave), int(k_slices), int(slab_tiles)), "tstgemm_set_tuning")
-
-
-def tstgemm_set_decode_lists(wide: bool = False):
-    """The small-M kernel reads the 32-bit TCSC lists (True) or their padded 16-bit copy where it can (False, default)."""
-    _check(_load().tstgemm_set_decode_lists(int(bool(wide))), "tstgemm_set_decode_lists")
-
-
-def tstgemm_profile_events(before=None, after=None):
-    """before / after: torch.cuda.Event(enable_timing=True) objects that have been recorded once (so that their
-    native handles exist), or None for both to switch the recording off."""
-    raw = [None if e is None else ctypes.c_void_p(e.cuda_event) for e in (before, after)]
-    _check(_load().tstgemm_profile_events(*raw), "tstgemm_profile_events")
 
 
 def tstgemm_probe_lds_read(iters: int, stream=None) -> int:

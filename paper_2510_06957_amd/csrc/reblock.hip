@@ -157,22 +157,26 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
-    const long long cells = (long long)l.n_pad * l.n_kblocks;
-    const unsigned grid = (unsigned)((cells + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(k_row_sets, dim3(grid), dim3(kThreads), 0, stream, d.col_start_pos, d.col_start_neg,
-                       d.row_index_pos, d.row_index_neg, d.masks, l.N, l.n_pad, l.n_kblocks);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const long long cut_cells = (long long)l.n_pad * (l.n_cuts + 1);
-    hipLaunchKernelGGL(k_list_cuts, dim3((unsigned)((cut_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
-                       d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.list_cuts, l.N, l.n_pad,
-                       l.n_cuts);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (l.nnz_pos > 0)
+    hipError_t e = hipSuccess;
+    if (l.forms & TCSC_FORM_ROWSETS) {
+        const long long cells = (long long)l.n_pad * l.n_kblocks;
+        const unsigned grid = (unsigned)((cells + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(k_row_sets, dim3(grid), dim3(kThreads), 0, stream, d.col_start_pos, d.col_start_neg,
+                           d.row_index_pos, d.row_index_neg, d.masks, l.N, l.n_pad, l.n_kblocks);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (l.forms & TCSC_FORM_CUTS) {
+        const long long cut_cells = (long long)l.n_pad * (l.n_cuts + 1);
+        hipLaunchKernelGGL(k_list_cuts, dim3((unsigned)((cut_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                           d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.list_cuts, l.N, l.n_pad,
+                           l.n_cuts);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if ((l.forms & TCSC_FORM_SIGNED) && l.nnz_pos > 0)
         hipLaunchKernelGGL(k_merge_signed<false>, dim3((unsigned)((l.nnz_pos + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                            stream, d.col_start_pos, d.col_start_neg, d.row_index_pos, d.row_index_neg, d.signed_index, l.N,
                            (int)l.nnz_pos);
-    if (l.nnz_neg > 0)
+    if ((l.forms & TCSC_FORM_SIGNED) && l.nnz_neg > 0)
         hipLaunchKernelGGL(k_merge_signed<true>, dim3((unsigned)((l.nnz_neg + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                            stream, d.col_start_neg, d.col_start_pos, d.row_index_neg, d.row_index_pos, d.signed_index, l.N,
                            (int)l.nnz_neg);
@@ -186,6 +190,7 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
                                d.col_start_neg, d.col_start16_neg, d.row_index_neg, d.row_index16_neg, l.N, (int)l.nnz16_neg, l.K);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
+    if (!(l.forms & TCSC_FORM_PACKED)) return hipSuccess;
     const long long pack_cells = (long long)l.n_pad * l.n_chunks5;
     hipLaunchKernelGGL(k_pack5, dim3((unsigned)((pack_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
                        d.masks, d.packed, l.n_pad, l.n_kblocks, l.n_chunks5);

@@ -22,17 +22,25 @@ void compute_layout(tcsc *t)
     l.n_cuts = (t->K + tst::kCutRows - 1) / tst::kCutRows;
     l.nnz_pos = (int64_t)t->row_index_pos.size();
     l.nnz_neg = (int64_t)t->row_index_neg.size();
+    uint32_t forms = t->forms;
+    if (forms & TCSC_FORM_PACKED) forms |= TCSC_FORM_ROWSETS;   // the codes are built from the row sets
     size_t off = 0;
-    auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    // a section of `bytes` bytes if the form is part of the buffer, else nothing at offset 0
+    auto place = [&](size_t bytes, bool present = true) {
+        if (!present) return (size_t)0;
+        size_t o = off;
+        off = align_up(off + bytes);
+        return o;
+    };
     l.off_col_start_pos = place(sizeof(int32_t) * (size_t)(t->N + 1));
     l.off_col_start_neg = place(sizeof(int32_t) * (size_t)(t->N + 1));
     // + slack: the kernels read the lists in groups of up to 64 entries
     l.off_row_index_pos = place(sizeof(int32_t) * (size_t)(l.nnz_pos + tst::kIndexSlack));
     l.off_row_index_neg = place(sizeof(int32_t) * (size_t)(l.nnz_neg + tst::kIndexSlack));
-    l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad);
-    l.off_list_cuts = place(2 * sizeof(int32_t) * (size_t)(l.n_cuts + 1) * (size_t)l.n_pad);
+    l.off_masks = place(2 * sizeof(uint64_t) * (size_t)l.n_kblocks * (size_t)l.n_pad, forms & TCSC_FORM_ROWSETS);
+    l.off_list_cuts = place(2 * sizeof(int32_t) * (size_t)(l.n_cuts + 1) * (size_t)l.n_pad, forms & TCSC_FORM_CUTS);
     // padded 16-bit lists: every column's list rounded up to 8 entries; the pad value K must fit in 16 bits
-    l.has_lists16 = t->K <= 65535 ? 1 : 0;
+    l.has_lists16 = ((forms & TCSC_FORM_LISTS16) && t->K <= 65535) ? 1 : 0;
     l.nnz16_pos = l.nnz16_neg = 0;
     t->col_start16_pos.clear();
     t->col_start16_neg.clear();
@@ -56,17 +64,19 @@ void compute_layout(tcsc *t)
             t->col_start16_neg.clear();
         }
     }
-    l.off_col_start16_pos = place(l.has_lists16 ? sizeof(int32_t) * (size_t)(t->N + 1) : 0);
-    l.off_col_start16_neg = place(l.has_lists16 ? sizeof(int32_t) * (size_t)(t->N + 1) : 0);
-    l.off_row_index16_pos = place(l.has_lists16 ? sizeof(uint16_t) * (size_t)(l.nnz16_pos + tst::kIndexSlack) : 0);
-    l.off_row_index16_neg = place(l.has_lists16 ? sizeof(uint16_t) * (size_t)(l.nnz16_neg + tst::kIndexSlack) : 0);
-    l.off_signed_index = place(sizeof(int32_t) * (size_t)(l.nnz_pos + l.nnz_neg + tst::kIndexSlack));
+    if (!l.has_lists16) forms &= ~TCSC_FORM_LISTS16;
+    l.off_col_start16_pos = place(sizeof(int32_t) * (size_t)(t->N + 1), l.has_lists16);
+    l.off_col_start16_neg = place(sizeof(int32_t) * (size_t)(t->N + 1), l.has_lists16);
+    l.off_row_index16_pos = place(sizeof(uint16_t) * (size_t)(l.nnz16_pos + tst::kIndexSlack), l.has_lists16);
+    l.off_row_index16_neg = place(sizeof(uint16_t) * (size_t)(l.nnz16_neg + tst::kIndexSlack), l.has_lists16);
+    l.off_signed_index = place(sizeof(int32_t) * (size_t)(l.nnz_pos + l.nnz_neg + tst::kIndexSlack), forms & TCSC_FORM_SIGNED);
     const int groups5 = (t->K + 4) / 5;
     l.n_chunks5 = (groups5 + tst::kChunk5 - 1) / tst::kChunk5;
-    l.off_packed = place((size_t)l.n_chunks5 * (size_t)l.n_pad * tst::kChunk5);
-    l.workspace_bytes = tst::workspace_bytes(l.n_kblocks);
-    l.off_workspace = place(l.workspace_bytes);
+    l.off_packed = place((size_t)l.n_chunks5 * (size_t)l.n_pad * tst::kChunk5, forms & TCSC_FORM_PACKED);
+    l.workspace_bytes = (forms & TCSC_FORM_WORKSPACE) ? tst::handle_workspace_bytes(l.n_kblocks) : 0;
+    l.off_workspace = place(l.workspace_bytes, forms & TCSC_FORM_WORKSPACE);
     l.total_bytes = off;
+    l.forms = forms;
 }
 
 // The structural rules of the format: monotone pointers starting at 0, rows inside [0,K),
@@ -116,7 +126,8 @@ int tcsc_build(const int8_t *W, int K, int N, tcsc_t **out)
             }
         }
         for (int n = 0; n < N; ++n) { cnt_p[n + 1] += cnt_p[n]; cnt_n[n + 1] += cnt_n[n]; }
-        if (cnt_p[N] > INT32_MAX || cnt_n[N] > INT32_MAX) return TSTGEMM_ETOOBIG;
+        // the inverted-index form numbers the entries of both signs together with 32-bit positions
+        if (cnt_p[N] + cnt_n[N] > INT32_MAX) return TSTGEMM_ETOOBIG;
         tcsc *t = new tcsc;
         t->K = K;
         t->N = N;
@@ -151,6 +162,7 @@ int tcsc_from_arrays(const int32_t *csp, const int32_t *csn, const int32_t *rip,
     for (int n = 0; n < N; ++n)
         if (csp[n + 1] < csp[n] || csn[n + 1] < csn[n]) return TSTGEMM_EFORMAT;
     if ((csp[N] > 0 && !rip) || (csn[N] > 0 && !rin)) return TSTGEMM_EINVAL;
+    if ((int64_t)csp[N] + (int64_t)csn[N] > INT32_MAX) return TSTGEMM_ETOOBIG;
     if (int rc = validate(csp, csn, rip, rin, K, N)) return rc;
     try {
         tcsc *t = new tcsc;
@@ -250,6 +262,35 @@ int tcsc_layout(const tcsc_t *t, tcsc_layout_t *out)
     return TSTGEMM_OK;
 }
 
+int tcsc_select_forms(tcsc_t *t, uint32_t forms)
+{
+    if (!t || (forms & ~TCSC_FORM_ALL)) return TSTGEMM_EINVAL;
+    t->forms = forms;
+    t->uploaded = false;
+    compute_layout(t);
+    return TSTGEMM_OK;
+}
+
+int tstgemm_workspace_bytes(int M, int K, int N, size_t *min_bytes, size_t *best_bytes)
+{
+    if (M < 1 || K < 1 || N < 1) return TSTGEMM_EINVAL;
+    size_t lo = 0, hi = 0;
+    if (M <= 8) {
+        hi = tst::packed_partial_bytes(N);
+    } else if (M <= 64) {
+        // one tile of X, then partial sums of at most 8 K slices of all (padded) columns, 32 or 64 rows each
+        lo = tst::small_tile_bytes(M, K);
+        const size_t n_pad = ((size_t)N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
+        hi = align_up(lo) + (size_t)tst::kMaxKSlices * n_pad * (M <= 32 ? 32 : 64) * sizeof(float);
+    } else {
+        const int n_pad = (N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
+        tst::large_workspace_bytes(M, K, n_pad, &lo, &hi);
+    }
+    if (min_bytes) *min_bytes = lo;
+    if (best_bytes) *best_bytes = hi;
+    return TSTGEMM_OK;
+}
+
 int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
 {
     if (!t || !dev_buf) return TSTGEMM_EINVAL;
@@ -283,74 +324,102 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
 
 namespace {
 
-int run(const float *X, const tcsc_t *t, const float *b, const tst::Activation &act, float *Y, int M, int K, int N,
-        void *stream)
+// One product: checks, the call's context from the options, dispatch on encoding and M.
+int run(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, const tstgemm_opts_t &o, void *stream)
 {
     if (!X || !t || !Y || M < 1) return TSTGEMM_EINVAL;
     if (K != t->K || N != t->N) return TSTGEMM_EINVAL;
+    if (o.encoding < 0 || o.encoding > 2 || (o.encoding != 0 && (M > 8 || o.alpha))) return TSTGEMM_EINVAL;
+    if (o.alpha && o.alpha_count != 1 && o.alpha_count != N) return TSTGEMM_EINVAL;
+    if (o.cols_per_wave != 0 && o.cols_per_wave != 1 && o.cols_per_wave != 2 && o.cols_per_wave != 4 && o.cols_per_wave != 8)
+        return TSTGEMM_EINVAL;
+    if (o.k_slices < 0 || o.k_slices > tst::kMaxKSlices || o.slab_tiles < 0) return TSTGEMM_EINVAL;
+    if ((o.event_before == nullptr) != (o.event_after == nullptr)) return TSTGEMM_EINVAL;
+    if (o.workspace && reinterpret_cast<uintptr_t>(o.workspace) % kAlign) return TSTGEMM_EINVAL;
     if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = tst::decode_supported(M) ? tst::launch_decode(X, t, b, act, Y, M, s)
-                   : M <= 64                ? tst::launch_small(X, t, b, act, Y, M, s)
-                                            : tst::launch_large(X, t, b, act, Y, M, s);
-    return e == hipSuccess ? TSTGEMM_OK : TSTGEMM_EHIP;
+    const tcsc_layout_t &l = t->layout;
+
+    tst::Call c{};
+    c.stream = static_cast<hipStream_t>(stream);
+    c.act = tst::Activation{o.alpha, (o.alpha && o.alpha_count != 1) ? 1 : 0};
+    if (o.workspace) {
+        c.ws = static_cast<char *>(o.workspace);
+        c.ws_bytes = o.workspace_bytes;
+    } else if (l.forms & TCSC_FORM_WORKSPACE) {
+        c.ws = static_cast<char *>(t->dev) + l.off_workspace;
+        c.ws_bytes = l.workspace_bytes;
+    }
+    c.cols_per_wave = o.cols_per_wave;
+    c.k_slices = o.k_slices;
+    c.slab_tiles = o.slab_tiles;
+    c.decode_wide_lists = o.decode_wide_lists != 0;
+    c.event_before = static_cast<hipEvent_t>(o.event_before);
+    c.event_after = static_cast<hipEvent_t>(o.event_after);
+
+    hipError_t e;
+    if (o.encoding == 1) {
+        if (!(l.forms & TCSC_FORM_SIGNED)) return TSTGEMM_ENOFORM;
+        e = tst::launch_decode_signed(X, t, b, Y, M, c);
+    } else if (o.encoding == 2) {
+        if (!(l.forms & TCSC_FORM_PACKED)) return TSTGEMM_ENOFORM;
+        e = tst::launch_packed(X, t, b, Y, M, c);
+    } else if (tst::decode_supported(M)) {
+        e = tst::launch_decode(X, t, b, Y, M, c);
+    } else if (M <= 64) {
+        if (!(l.forms & TCSC_FORM_CUTS)) return TSTGEMM_ENOFORM;
+        e = tst::launch_small(X, t, b, Y, M, c);
+    } else {
+        if (!(l.forms & TCSC_FORM_ROWSETS)) return TSTGEMM_ENOFORM;
+        e = tst::launch_large(X, t, b, Y, M, c);
+    }
+    return e == hipSuccess ? TSTGEMM_OK : e == tst::kErrWorkspace ? TSTGEMM_EWORKSPACE : TSTGEMM_EHIP;
+}
+
+tstgemm_opts_t default_opts()
+{
+    tstgemm_opts_t o{};
+    o.struct_size = sizeof(o);
+    return o;
 }
 
 }  // namespace
 
 extern "C" {
 
+int tstgemm_ex(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, const tstgemm_opts_t *opts,
+               void *stream)
+{
+    if (opts && opts->struct_size != sizeof(tstgemm_opts_t)) return TSTGEMM_EINVAL;
+    return run(X, t, b, Y, M, K, N, opts ? *opts : default_opts(), stream);
+}
+
 int tstgemm(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
 {
-    return run(X, t, b, tst::Activation{nullptr, 0}, Y, M, K, N, stream);
+    return run(X, t, b, Y, M, K, N, default_opts(), stream);
 }
 
 int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *alpha, int alpha_count, float *Y, int M,
                   int K, int N, void *stream)
 {
     if (!alpha || (alpha_count != 1 && alpha_count != N)) return TSTGEMM_EINVAL;
-    return run(X, t, b, tst::Activation{alpha, alpha_count == 1 ? 0 : 1}, Y, M, K, N, stream);
+    tstgemm_opts_t o = default_opts();
+    o.alpha = alpha;
+    o.alpha_count = alpha_count;
+    return run(X, t, b, Y, M, K, N, o, stream);
 }
 
 int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
 {
-    if (!X || !t || !Y || M < 1 || M > 8 || K != t->K || N != t->N) return TSTGEMM_EINVAL;
-    if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
-    return tst::launch_decode_signed(X, t, b, Y, M, static_cast<hipStream_t>(stream)) == hipSuccess ? TSTGEMM_OK
-                                                                                                  : TSTGEMM_EHIP;
+    tstgemm_opts_t o = default_opts();
+    o.encoding = 1;
+    return run(X, t, b, Y, M, K, N, o, stream);
 }
 
 int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream)
 {
-    if (!X || !t || !Y || M < 1 || M > 8 || K != t->K || N != t->N) return TSTGEMM_EINVAL;
-    if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
-    return tst::launch_packed(X, t, b, Y, M, static_cast<hipStream_t>(stream)) == hipSuccess ? TSTGEMM_OK
-                                                                                           : TSTGEMM_EHIP;
-}
-
-int tstgemm_set_tuning(int cols_per_wave, int k_slices, int slab_tiles)
-{
-    if (cols_per_wave != 0 && cols_per_wave != 1 && cols_per_wave != 2 && cols_per_wave != 4 && cols_per_wave != 8)
-        return TSTGEMM_EINVAL;
-    if (k_slices < 0 || k_slices > 8 || slab_tiles < 0) return TSTGEMM_EINVAL;
-    tst::g_cols_per_wave = cols_per_wave;
-    tst::g_k_slices = k_slices;
-    tst::g_slab_tiles = slab_tiles;
-    return TSTGEMM_OK;
-}
-
-int tstgemm_set_decode_lists(int wide)
-{
-    tst::g_decode_wide_lists = wide != 0;
-    return TSTGEMM_OK;
-}
-
-int tstgemm_profile_events(void *before, void *after)
-{
-    if ((before == nullptr) != (after == nullptr)) return TSTGEMM_EINVAL;
-    tst::g_event_before = static_cast<hipEvent_t>(before);
-    tst::g_event_after = static_cast<hipEvent_t>(after);
-    return TSTGEMM_OK;
+    tstgemm_opts_t o = default_opts();
+    o.encoding = 2;
+    return run(X, t, b, Y, M, K, N, o, stream);
 }
 
 void tcsc_destroy(tcsc_t *t) { delete t; }
@@ -365,6 +434,8 @@ const char *tcsc_strerror(int code)
     case TSTGEMM_EHIP: return "a HIP runtime call failed";
     case TSTGEMM_ENOMEM: return "out of host memory, or device buffer too small";
     case TSTGEMM_ETOOBIG: return "matrix too large for 32-bit TCSC pointers";
+    case TSTGEMM_ENOFORM: return "the device form this call reads was not selected when the matrix was uploaded";
+    case TSTGEMM_EWORKSPACE: return "no workspace, or one smaller than tstgemm_workspace_bytes() gives as the minimum";
     default: return "unknown tstgemm error code";
     }
 }

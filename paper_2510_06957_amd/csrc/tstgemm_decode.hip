@@ -20,6 +20,8 @@
 //     bias is added once, last (then the optional PReLU), and one lane per row stores the result.
 // The same kernel also runs on the paper's inverted-index form (Sec. 3): one merged list per column
 // whose entries carry their sign (i for +1, ~i for -1); the sign bit is flipped into the operand.
+#include <atomic>
+
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -205,16 +207,22 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
 }
 
 template <int MM, bool CHUNKED, int FORM>
-hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int kc, size_t lds,
-                         hipStream_t stream)
+hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, float *Y, int kc, size_t lds, const Call &c)
 {
     const DeviceTcsc d = device_view(t);
-    static bool attr_set = false;
-    if (!attr_set) {
+    const hipStream_t stream = c.stream;
+    const Activation &act = c.act;
+    // the kernel's LDS limit is an attribute of the function on a device: set once per device (bit = device number;
+    // devices beyond 63 set it on every call)
+    static std::atomic<unsigned long long> attr_devices{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    const unsigned long long bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0;
+    if ((attr_devices.load(std::memory_order_relaxed) & bit) == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM, CHUNKED, FORM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_devices.fetch_or(bit, std::memory_order_relaxed);
     }
     const int per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
     int grid = compute_units() * per_cu;
@@ -225,7 +233,7 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Ac
     const int rounds = (need + grid - 1) / grid;
     grid = (need + rounds - 1) / rounds;
     hipError_t e;
-    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
+    if ((e = c.record_before()) != hipSuccess) return e;
     const int32_t *cs_pos = FORM == 2 ? d.col_start16_pos : d.col_start_pos;
     const int32_t *cs_neg = FORM == 2 ? d.col_start16_neg : d.col_start_neg;
     const void *lists_pos = FORM == 1 ? static_cast<const void *>(d.signed_index)
@@ -235,33 +243,32 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, const Ac
     hipLaunchKernelGGL((k_decode<MM, CHUNKED, FORM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, cs_pos, cs_neg,
                        lists_pos, lists_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N, kc);
     e = hipGetLastError();
-    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    if (e == hipSuccess) e = c.record_after();
     return e;
 }
 
 template <int MM, int FORM>
-hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, const Call &c)
 {
     const int kc = t->K < chunk_rows<MM>() ? t->K : chunk_rows<MM>();
     const size_t lds = (size_t)(kc + 1) * MM * sizeof(float);
     if (t->K > kc)   // K in chunks: the 32-bit lists (the padded 16-bit ones are for X whole in the LDS)
-        return launch_kernel<MM, true, FORM == 2 ? 0 : FORM>(X, t, b, act, Y, kc, lds, stream);
-    return launch_kernel<MM, false, FORM>(X, t, b, act, Y, kc, lds, stream);
+        return launch_kernel<MM, true, FORM == 2 ? 0 : FORM>(X, t, b, Y, kc, lds, c);
+    return launch_kernel<MM, false, FORM>(X, t, b, Y, kc, lds, c);
 }
 
 template <int FORM>
-hipError_t launch_m(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
-                    hipStream_t stream)
+hipError_t launch_m(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
     switch (M) {
-    case 1: return launch<1, FORM>(X, t, b, act, Y, stream);
-    case 2: return launch<2, FORM>(X, t, b, act, Y, stream);
-    case 3: return launch<3, FORM>(X, t, b, act, Y, stream);
-    case 4: return launch<4, FORM>(X, t, b, act, Y, stream);
-    case 5: return launch<5, FORM>(X, t, b, act, Y, stream);
-    case 6: return launch<6, FORM>(X, t, b, act, Y, stream);
-    case 7: return launch<7, FORM>(X, t, b, act, Y, stream);
-    case 8: return launch<8, FORM>(X, t, b, act, Y, stream);
+    case 1: return launch<1, FORM>(X, t, b, Y, c);
+    case 2: return launch<2, FORM>(X, t, b, Y, c);
+    case 3: return launch<3, FORM>(X, t, b, Y, c);
+    case 4: return launch<4, FORM>(X, t, b, Y, c);
+    case 5: return launch<5, FORM>(X, t, b, Y, c);
+    case 6: return launch<6, FORM>(X, t, b, Y, c);
+    case 7: return launch<7, FORM>(X, t, b, Y, c);
+    case 8: return launch<8, FORM>(X, t, b, Y, c);
     default: return hipErrorInvalidValue;
     }
 }
@@ -270,17 +277,16 @@ hipError_t launch_m(const float *X, const tcsc *t, const float *b, const Activat
 
 bool decode_supported(int M) { return M <= 8; }
 
-hipError_t launch_decode(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
-                         hipStream_t stream)
+hipError_t launch_decode(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
     // the padded 16-bit copy of the lists, if the matrix has one (K <= 65535): half the bytes
-    if (t->layout.has_lists16 && !g_decode_wide_lists) return launch_m<2>(X, t, b, act, Y, M, stream);
-    return launch_m<0>(X, t, b, act, Y, M, stream);
+    if (t->layout.has_lists16 && !c.decode_wide_lists) return launch_m<2>(X, t, b, Y, M, c);
+    return launch_m<0>(X, t, b, Y, M, c);
 }
 
-hipError_t launch_decode_signed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+hipError_t launch_decode_signed(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
-    return launch_m<1>(X, t, b, Activation{nullptr, 0}, Y, M, stream);
+    return launch_m<1>(X, t, b, Y, M, c);
 }
 
 }  // namespace tst

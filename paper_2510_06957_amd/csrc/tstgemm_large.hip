@@ -36,9 +36,6 @@
 
 namespace tst {
 
-int g_cols_per_wave = 0, g_k_slices = 0, g_slab_tiles = 0, g_decode_wide_lists = 0;
-hipEvent_t g_event_before = nullptr, g_event_after = nullptr;
-
 namespace {
 
 constexpr int NW = 16;        // wavefronts per workgroup
@@ -295,25 +292,25 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     }
 }
 
-// One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles must fit the workspace.
+// One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles fit wp.xt.
 template <int R, int NCW, int GMAX = 8>
-hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int rows, int k_slices,
-                  hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int rows, int k_slices, const WorkspacePlan &wp,
+                  const Call &c)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
     constexpr int TM = 64 * R;
     const int k_pad = l.n_kblocks * kKBlock;
     const long long m_tiles = (rows + TM - 1) / TM;
-    if ((size_t)m_tiles * k_pad * TM * sizeof(float) > d.xt_capacity) return hipErrorInvalidValue;
+    if (m_tiles * TM > wp.slab_rows) return hipErrorInvalidValue;
 
-    hipError_t e = launch_pack(X, d.xt, rows, l.K, k_pad, TM, stream);
+    hipError_t e = launch_pack(X, wp.xt, rows, l.K, k_pad, TM, c.stream);
     if (e != hipSuccess) return e;
 
     LargeArgs a;
-    a.xt = d.xt; a.masks = d.masks; a.b = b; a.Y = Y;
-    a.alpha = act.alpha; a.alpha_stride = act.alpha_stride;
-    a.partials = d.partials;
+    a.xt = wp.xt; a.masks = d.masks; a.b = b; a.Y = Y;
+    a.alpha = c.act.alpha; a.alpha_stride = c.act.alpha_stride;
+    a.partials = wp.partials;
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     if constexpr (NCW == 8) {
         // 128 columns per workgroup: the reduction kernel has no tile of that width, so K is never sliced here
@@ -324,72 +321,84 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     const long long groups = m_tiles * a.n_colgroups;
     if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
     const size_t slice_bytes = (size_t)groups * NW * NCW * TM * sizeof(float);
-    if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
+    if (k_slices > 1 && slice_bytes * k_slices > wp.partial_bytes) k_slices = (int)(wp.partial_bytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.kb_per_slice = (l.n_kblocks + k_slices - 1) / k_slices;
     const long long grid = groups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
-    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_large<R, NCW, GMAX>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    if ((e = c.record_before()) != hipSuccess) return e;
+    hipLaunchKernelGGL((k_large<R, NCW, GMAX>), dim3((unsigned)grid), dim3(NT), 0, c.stream, a);
     e = hipGetLastError();
-    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    if (e == hipSuccess) e = c.record_after();
     if (e != hipSuccess || k_slices == 1) return e;
-    return launch_reduce(NW * NCW, d.partials, b, act, Y, rows, l.N, (int)m_tiles, a.n_colgroups, k_slices, TM, stream);
+    return launch_reduce(NW * NCW, wp.partials, b, c.act, Y, rows, l.N, (int)m_tiles, a.n_colgroups, k_slices, TM, c.stream);
 }
 
-// Launch shape: 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave
-// compute units idle, into as few slices as fill them.  X is processed in slabs of as many row tiles as the
-// workspace holds.  With 8 columns per wavefront (128 per workgroup, gather groups of at most 4) a workgroup
+// Columns per wavefront and K slices for `m_tiles` row tiles processed together.
+// 4 columns per wavefront (64 per workgroup); K is sliced only when rows x columns alone leave compute units idle, into
+// as few slices as fill them.  With 8 columns per wavefront (128 per workgroup, gather groups of at most 4) a workgroup
 // exchanges its tile half as often per column; that shape is taken when the column count allows it, rows x columns
 // fill the chip without slicing K, and the estimate below says it is faster.  Measured on M = 4096, K = 4096,
 // N = 8192 (whole rounds of workgroups in both shapes), time in us against the density d: 3760 d + 520 with 4
 // columns, 3966 d + 316 with 8 -- 4 % faster at d = 0.5, 31 % at 1/16; the estimate scales these with the number of
 // rounds of workgroups each shape needs (a last round that is partly filled costs a whole one).
-template <int R>
-hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, hipStream_t stream)
+struct Shape {
+    int ncw, k_slices;
+};
+inline Shape choose_shape(const tcsc_layout_t &l, long long m_tiles, const Call &c)
 {
-    const tcsc_layout_t &l = t->layout;
-    const DeviceTcsc d = device_view(t);
-    constexpr int TM = 64 * R;
     const bool wide_fits = l.n_pad % (NW * 8) == 0;
     const double density = (double)(l.nnz_pos + l.nnz_neg) / ((double)l.K * (double)l.N);
     const double gain8 = (3760.0 * density + 520.0) / (3966.0 * density + 316.0);   // time of a 64-column pair / time of a 128-column workgroup
+    const int slots = 2 * compute_units();   // two workgroups per compute unit
+    int ncw = c.cols_per_wave ? c.cols_per_wave : 4;
+    if (c.cols_per_wave == 0 && wide_fits) {
+        const long long groups8 = m_tiles * (l.n_pad / (NW * 8)), groups4 = 2 * groups8;
+        const long long rounds8 = (groups8 + slots - 1) / slots, rounds4 = (groups4 + slots - 1) / slots;
+        if (groups8 >= slots && 2.0 * (double)rounds8 <= (double)rounds4 * gain8) ncw = 8;
+        // one workgroup per compute unit only: still ahead where the lists are very short (measured: 10 % at a
+        // density of 1/16 on M = 2048, N = 4096 and on M = 1024, N = 8192; a tie at 1/8; 7 % behind at 1/2)
+        else if (groups8 < slots && 2 * groups8 >= slots && gain8 >= 1.3) ncw = 8;
+    }
+    if (ncw == 8 && !wide_fits) ncw = 4;
+    int k_slices = 1;
+    if (ncw != 8) {
+        k_slices = c.k_slices ? c.k_slices : slices_to_fill(m_tiles * (l.n_pad / (NW * ncw)), slots);
+        if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;
+    }
+    return Shape{ncw, k_slices};
+}
+
+// X is processed in slabs of as many row tiles as the workspace holds next to the partial sums (one slab if the
+// workspace has room for everything the call's launch shape needs).
+template <int R>
+hipError_t pick(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
+{
+    const tcsc_layout_t &l = t->layout;
+    constexpr int TM = 64 * R;
     const size_t tile_bytes = (size_t)l.n_kblocks * kKBlock * TM * sizeof(float);
-    long long slab_rows = (long long)(d.xt_capacity / tile_bytes) * TM;
-    if (slab_rows < TM) return hipErrorInvalidValue;
+    const long long m_tiles_all = ((long long)M + TM - 1) / TM;
+    const Shape whole = choose_shape(l, m_tiles_all, c);
+    const size_t partial_want =
+        whole.k_slices > 1 ? (size_t)whole.k_slices * m_tiles_all * TM * l.n_pad * sizeof(float) : 0;
+    WorkspacePlan wp = plan_workspace(c, tile_bytes, m_tiles_all, TM, partial_want);
+    if (wp.slab_rows < TM) return kErrWorkspace;
+    long long slab_rows = wp.slab_rows;
     if (slab_rows > 65535LL * 64) slab_rows = 65535LL * 64 / TM * TM;
-    if (g_slab_tiles > 0 && slab_rows > (long long)g_slab_tiles * TM) slab_rows = (long long)g_slab_tiles * TM;
+    if (c.slab_tiles > 0 && slab_rows > (long long)c.slab_tiles * TM) slab_rows = (long long)c.slab_tiles * TM;
     for (long long m_begin = 0; m_begin < M; m_begin += slab_rows) {
         const int rows = (int)((M - m_begin) < slab_rows ? (M - m_begin) : slab_rows);
-        const long long m_tiles = (rows + TM - 1) / TM;
-        const int slots = 2 * compute_units();   // two workgroups per compute unit
-        int ncw = g_cols_per_wave ? g_cols_per_wave : 4;
-        if (g_cols_per_wave == 0 && wide_fits) {
-            const long long groups8 = m_tiles * (l.n_pad / (NW * 8)), groups4 = 2 * groups8;
-            const long long rounds8 = (groups8 + slots - 1) / slots, rounds4 = (groups4 + slots - 1) / slots;
-            if (groups8 >= slots && 2.0 * (double)rounds8 <= (double)rounds4 * gain8) ncw = 8;
-            // one workgroup per compute unit only: still ahead where the lists are very short (measured: 10 % at a
-            // density of 1/16 on M = 2048, N = 4096 and on M = 1024, N = 8192; a tie at 1/8; 7 % behind at 1/2)
-            else if (groups8 < slots && 2 * groups8 >= slots && gain8 >= 1.3) ncw = 8;
-        }
-        if (ncw == 8 && !wide_fits) ncw = 4;
-        const long long groups = m_tiles * (l.n_pad / (NW * ncw));
-        int k_slices = g_k_slices;
-        if (k_slices == 0) {
-            k_slices = groups >= slots ? 1 : (int)((slots + groups - 1) / groups);
-            if (k_slices > 8) k_slices = 8;
-        }
-        if (k_slices > l.n_kblocks) k_slices = l.n_kblocks;
+        const Shape s = choose_shape(l, (rows + TM - 1) / TM, c);
         const float *Xs = X + (size_t)m_begin * l.K;
         float *Ys = Y + (size_t)m_begin * l.N;
         hipError_t e;
-        switch (ncw) {
-        case 1: e = launch<R, 1>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
-        case 2: e = launch<R, 2>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
-        case 8: e = launch<R, 8, 4>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
-        default: e = launch<R, 4>(Xs, t, b, act, Ys, rows, k_slices, stream); break;
+        switch (s.ncw) {
+        case 1: e = launch<R, 1>(Xs, t, b, Ys, rows, s.k_slices, wp, c); break;
+        case 2: e = launch<R, 2>(Xs, t, b, Ys, rows, s.k_slices, wp, c); break;
+        case 8: e = launch<R, 8, 4>(Xs, t, b, Ys, rows, s.k_slices, wp, c); break;
+        default: e = launch<R, 4>(Xs, t, b, Ys, rows, s.k_slices, wp, c); break;
         }
         if (e != hipSuccess) return e;
     }
@@ -398,11 +407,25 @@ hipError_t pick(const float *X, const tcsc *t, const float *b, const Activation 
 
 }  // namespace
 
-hipError_t launch_large(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
-                        hipStream_t stream)
+hipError_t launch_large(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
-    if (M <= 128) return pick<2>(X, t, b, act, Y, M, stream);
-    return pick<4>(X, t, b, act, Y, M, stream);
+    if (M <= 128) return pick<2>(X, t, b, Y, M, c);
+    return pick<4>(X, t, b, Y, M, c);
+}
+
+// Scratch memory of the large-M path: the least it runs with, and what one slab of every shape it would choose needs.
+void large_workspace_bytes(int M, int K, int n_pad, size_t *min_bytes, size_t *best_bytes)
+{
+    const int TM = M <= 128 ? 128 : 256;
+    const long long n_kblocks = ((long long)K + kKBlock - 1) / kKBlock;
+    const size_t tile_bytes = (size_t)n_kblocks * kKBlock * TM * sizeof(float);
+    const long long m_tiles = ((long long)M + TM - 1) / TM;
+    // the most K slices any built-in shape takes: 64-column workgroups
+    long long k_slices = slices_to_fill(m_tiles * (n_pad / (NW * 4)), 2 * compute_units());
+    if (k_slices > n_kblocks) k_slices = n_kblocks;
+    const size_t partial = k_slices > 1 ? (size_t)k_slices * m_tiles * TM * n_pad * sizeof(float) : 0;
+    *min_bytes = tile_bytes;
+    *best_bytes = ((size_t)m_tiles * tile_bytes + 255) / 256 * 256 + partial;
 }
 
 }  // namespace tst

@@ -163,48 +163,57 @@ k_packed(const float *__restrict__ X, const uint8_t *__restrict__ packed, const 
     }
 }
 
-template <int MM> hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, hipStream_t stream)
+template <int MM> hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, const Call &c)
 {
     const tcsc_layout_t &l = t->layout;
     const DeviceTcsc d = device_view(t);
+    const hipStream_t stream = c.stream;
+    float *const partials = reinterpret_cast<float *>(c.ws);   // may be absent: K is then not dealt to several workgroups
     const int n_colgroups = l.n_pad / 64;
     // parts of K per column group: only if the column groups leave at least half of the compute units idle (with 172
     // groups on 256 units three parts were slower than one) and a column holds enough work (rows of X x pieces) to
     // outweigh the second launch; every wavefront must still get a piece
-    int k_parts = g_k_slices;
+    int k_parts = c.k_slices;
     if (k_parts == 0) {
         const int cus = compute_units();
         k_parts = (2 * n_colgroups <= cus && MM * l.n_chunks5 >= 400) ? cus / n_colgroups : 1;
         if (k_parts > 4) k_parts = 4;
     }
     if (k_parts > l.n_chunks5 / kWaves) k_parts = l.n_chunks5 / kWaves;
-    if ((size_t)n_colgroups * k_parts * 64 * kPartRows * sizeof(float) > kPartialBytes) k_parts = 1;
+    if (partials == nullptr || (size_t)n_colgroups * k_parts * 64 * kPartRows * sizeof(float) > c.ws_bytes) k_parts = 1;
     if (k_parts < 1) k_parts = 1;
     hipError_t e;
-    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
+    if ((e = c.record_before()) != hipSuccess) return e;
     hipLaunchKernelGGL((k_packed<MM>), dim3((unsigned)(n_colgroups * k_parts)), dim3(kThreads), 0, stream, X, d.packed, b, Y,
-                       d.partials, l.K, l.N, l.n_pad, l.n_chunks5, k_parts);
+                       partials, l.K, l.N, l.n_pad, l.n_chunks5, k_parts);
     e = hipGetLastError();
-    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    if (e == hipSuccess) e = c.record_after();
     if (e != hipSuccess || k_parts == 1) return e;
-    return launch_reduce(64, d.partials, b, Activation{nullptr, 0}, Y, MM, l.N, 1, n_colgroups, k_parts, kPartRows, stream);
+    return launch_reduce(64, partials, b, Activation{nullptr, 0}, Y, MM, l.N, 1, n_colgroups, k_parts, kPartRows, stream);
 }
 
 }  // namespace
 
-hipError_t launch_packed(const float *X, const tcsc *t, const float *b, float *Y, int M, hipStream_t stream)
+hipError_t launch_packed(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
     switch (M) {
-    case 1: return launch<1>(X, t, b, Y, stream);
-    case 2: return launch<2>(X, t, b, Y, stream);
-    case 3: return launch<3>(X, t, b, Y, stream);
-    case 4: return launch<4>(X, t, b, Y, stream);
-    case 5: return launch<5>(X, t, b, Y, stream);
-    case 6: return launch<6>(X, t, b, Y, stream);
-    case 7: return launch<7>(X, t, b, Y, stream);
-    case 8: return launch<8>(X, t, b, Y, stream);
+    case 1: return launch<1>(X, t, b, Y, c);
+    case 2: return launch<2>(X, t, b, Y, c);
+    case 3: return launch<3>(X, t, b, Y, c);
+    case 4: return launch<4>(X, t, b, Y, c);
+    case 5: return launch<5>(X, t, b, Y, c);
+    case 6: return launch<6>(X, t, b, Y, c);
+    case 7: return launch<7>(X, t, b, Y, c);
+    case 8: return launch<8>(X, t, b, Y, c);
     default: return hipErrorInvalidValue;
     }
+}
+
+// At most 4 workgroups per group of 64 columns write partial sums of kPartRows rows each.
+size_t packed_partial_bytes(int N)
+{
+    const size_t n_colgroups = ((size_t)N + 63) / 64;
+    return n_colgroups * kMaxKSlices * 64 * kPartRows * sizeof(float);
 }
 
 }  // namespace tst

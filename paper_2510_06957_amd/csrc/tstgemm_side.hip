@@ -1,6 +1,8 @@
 // Side kernels of the tiled gather-add paths of the sparse ternary GEMM  Y = X W + b  (Eq. 1 of the paper):
 // k_pack_x, which lays X out as transposed row tiles before the main kernel, and k_reduce, which adds the K slices of a
 // split-K run in a fixed order, adds the bias (once, last), applies the optional PReLU and writes Y.
+#include <atomic>
+
 #include "tstgemm_internal.h"
 
 namespace tst {
@@ -129,18 +131,20 @@ k_reduce(const float *__restrict__ P, const float *__restrict__ b, const float *
 
 }  // namespace
 
+// Compute units of the current device; remembered per device (read-only facts about the machine).
 int compute_units()
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
+    constexpr int kDevices = 64;
+    static std::atomic<int> cus[kDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool cached = dev >= 0 && dev < kDevices;
+    int n = cached ? cus[dev].load(std::memory_order_relaxed) : 0;
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        if (cached) cus[dev].store(n, std::memory_order_relaxed);
     }
-    return cus;
+    return n;
 }
 
 

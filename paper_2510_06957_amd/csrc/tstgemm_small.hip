@@ -221,8 +221,7 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 }
 
 template <int NCW, int G>
-hipError_t launch(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M, int k_slices,
-                  hipStream_t stream)
+hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M, int k_slices, const Call &c)
 {
     using geo = Geo<G>;
     constexpr int TM = geo::TM;
@@ -230,31 +229,36 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
     const DeviceTcsc d = device_view(t);
     const int n_blocks = (l.K + geo::ROWS - 1) / geo::ROWS;
     const int k_pad = n_blocks * geo::ROWS;
-    if ((size_t)k_pad * TM * sizeof(float) > d.xt_capacity || M > TM) return hipErrorInvalidValue;
-    hipError_t e = launch_pack(X, d.xt, M, l.K, k_pad, TM, stream);
+    if (M > TM) return hipErrorInvalidValue;
+    // workspace: the one tile of X, then whatever is left for the partial sums of the K slices
+    const WorkspacePlan wp = plan_workspace(c, (size_t)k_pad * TM * sizeof(float), 1, TM, 0);
+    if (wp.slab_rows < TM) return kErrWorkspace;
+    const hipStream_t stream = c.stream;
+    const Activation &act = c.act;
+    hipError_t e = launch_pack(X, wp.xt, M, l.K, k_pad, TM, stream);
     if (e != hipSuccess) return e;
 
     SmallArgs a;
-    a.xt = d.xt; a.cuts = d.list_cuts; a.rip = d.row_index_pos; a.rin = d.row_index_neg;
-    a.b = b; a.alpha = act.alpha; a.alpha_stride = act.alpha_stride; a.Y = Y; a.partials = d.partials;
+    a.xt = wp.xt; a.cuts = d.list_cuts; a.rip = d.row_index_pos; a.rin = d.row_index_neg;
+    a.b = b; a.alpha = act.alpha; a.alpha_stride = act.alpha_stride; a.Y = Y; a.partials = wp.partials;
     a.M = M; a.N = l.N; a.n_pad = l.n_pad; a.n_cuts = l.n_cuts; a.n_blocks = n_blocks;
     a.n_colgroups = l.n_pad / (NW * NCW);
     if (k_slices > n_blocks) k_slices = n_blocks;
     if (k_slices > kMaxKSlices) k_slices = kMaxKSlices;
     const size_t slice_bytes = (size_t)a.n_colgroups * NW * NCW * geo::PR * sizeof(float);
-    if (k_slices > 1 && slice_bytes * k_slices > kPartialBytes) k_slices = (int)(kPartialBytes / slice_bytes);
+    if (k_slices > 1 && slice_bytes * k_slices > wp.partial_bytes) k_slices = (int)(wp.partial_bytes / slice_bytes);
     if (k_slices < 1) k_slices = 1;
     a.k_slices = k_slices;
     a.blocks_per_slice = (n_blocks + k_slices - 1) / k_slices;
     const long long grid = (long long)a.n_colgroups * k_slices;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
-    if (g_event_before && (e = hipEventRecord(g_event_before, stream)) != hipSuccess) return e;
+    if ((e = c.record_before()) != hipSuccess) return e;
     hipLaunchKernelGGL((k_small<NCW, G>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
-    if (e == hipSuccess && g_event_after) e = hipEventRecord(g_event_after, stream);
+    if (e == hipSuccess) e = c.record_after();
     if (e != hipSuccess || k_slices == 1) return e;
-    return launch_reduce(NW * NCW, d.partials, b, act, Y, M, l.N, 1, a.n_colgroups, k_slices, geo::PR, stream);
+    return launch_reduce(NW * NCW, wp.partials, b, act, Y, M, l.N, 1, a.n_colgroups, k_slices, geo::PR, stream);
 }
 
 }  // namespace
@@ -264,16 +268,15 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, const Activatio
 // workgroup: a block of the tile in the LDS serves twice the columns, half the exchanges per column) when that still
 // fills the chip with at most 8 slices of at least 4 blocks each; else 2; a short K (at most four list cuts) is not
 // sliced and takes one column per wavefront, which saves the reduction kernel.
-hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Activation &act, float *Y, int M,
-                        hipStream_t stream)
+hipError_t launch_small(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c)
 {
     if (M > 64) return hipErrorInvalidValue;
     const tcsc_layout_t &l = t->layout;
     const bool short_k = l.n_cuts <= 4;
     const int G = M <= 16 ? 16 : M <= 32 ? 8 : 4;
     const int slots = 2 * compute_units();
-    int ncw = g_cols_per_wave ? (g_cols_per_wave == 1 ? 1 : g_cols_per_wave == 2 ? 2 : 4) : (short_k ? 1 : 2);
-    if (g_cols_per_wave == 0 && !short_k) {
+    int ncw = c.cols_per_wave ? (c.cols_per_wave == 1 ? 1 : c.cols_per_wave == 2 ? 2 : 4) : (short_k ? 1 : 2);
+    if (c.cols_per_wave == 0 && !short_k) {
         const int block_rows = STAGE / (4 * (256 / G));            // rows of W per block of the tile
         const long long n_blocks = (l.K + block_rows - 1) / block_rows;
         const long long groups4 = l.n_pad / (NW * 4);
@@ -281,19 +284,28 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, const Act
         if (slices4 <= kMaxKSlices && n_blocks >= 4 * slices4) ncw = 4;
     }
     const long long groups = l.n_pad / (NW * ncw);
-    int k_slices = g_k_slices;
+    int k_slices = c.k_slices;
     if (k_slices == 0) k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
     switch (G * 8 + ncw) {
-    case 16 * 8 + 1: return launch<1, 16>(X, t, b, act, Y, M, k_slices, stream);
-    case 16 * 8 + 2: return launch<2, 16>(X, t, b, act, Y, M, k_slices, stream);
-    case 16 * 8 + 4: return launch<4, 16>(X, t, b, act, Y, M, k_slices, stream);
-    case 8 * 8 + 1: return launch<1, 8>(X, t, b, act, Y, M, k_slices, stream);
-    case 8 * 8 + 2: return launch<2, 8>(X, t, b, act, Y, M, k_slices, stream);
-    case 8 * 8 + 4: return launch<4, 8>(X, t, b, act, Y, M, k_slices, stream);
-    case 4 * 8 + 1: return launch<1, 4>(X, t, b, act, Y, M, k_slices, stream);
-    case 4 * 8 + 2: return launch<2, 4>(X, t, b, act, Y, M, k_slices, stream);
-    default: return launch<4, 4>(X, t, b, act, Y, M, k_slices, stream);
+    case 16 * 8 + 1: return launch<1, 16>(X, t, b, Y, M, k_slices, c);
+    case 16 * 8 + 2: return launch<2, 16>(X, t, b, Y, M, k_slices, c);
+    case 16 * 8 + 4: return launch<4, 16>(X, t, b, Y, M, k_slices, c);
+    case 8 * 8 + 1: return launch<1, 8>(X, t, b, Y, M, k_slices, c);
+    case 8 * 8 + 2: return launch<2, 8>(X, t, b, Y, M, k_slices, c);
+    case 8 * 8 + 4: return launch<4, 8>(X, t, b, Y, M, k_slices, c);
+    case 4 * 8 + 1: return launch<1, 4>(X, t, b, Y, M, k_slices, c);
+    case 4 * 8 + 2: return launch<2, 4>(X, t, b, Y, M, k_slices, c);
+    default: return launch<4, 4>(X, t, b, Y, M, k_slices, c);
     }
+}
+
+// Bytes of the one tile of X (M <= 64 rows: 64, 32 or 16 rows per tile) over K padded to whole blocks.
+size_t small_tile_bytes(int M, int K)
+{
+    const int TM = M <= 16 ? 16 : M <= 32 ? 32 : 64;
+    const int block_rows = STAGE / (4 * TM);
+    const long long n_blocks = ((long long)K + block_rows - 1) / block_rows;
+    return (size_t)n_blocks * block_rows * TM * sizeof(float);
 }
 
 }  // namespace tst

@@ -7,8 +7,9 @@ import paper_2510_06957_amd as tg
 REL_TOL = 1e-5   # |Y_gpu - Y_oracle| <= REL_TOL * (sum_k |X[m,k] W[k,n]| + |b[n]|), per element
 
 
-def gpu_tstgemm(W, X, b, handle=None, alpha=None):
-    """Y (numpy float32) from the HIP library for host inputs; returns (Y, handle).  alpha: PReLU slopes or None."""
+def gpu_tstgemm(W, X, b, handle=None, alpha=None, **options):
+    """Y (numpy float32) from the HIP library for host inputs; returns (Y, handle).  alpha: PReLU slopes or None;
+    options: per-call options of the binding's tstgemm() (launch shape, workspace, list width)."""
     import torch
     if handle is None:
         handle = tg.tcsc_upload(tg.tcsc_build(W))
@@ -16,7 +17,7 @@ def gpu_tstgemm(W, X, b, handle=None, alpha=None):
     bd = None if b is None else torch.from_numpy(np.ascontiguousarray(b)).cuda()
     Yd = torch.full((X.shape[0], W.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
     ad = None if alpha is None else torch.from_numpy(np.ascontiguousarray(np.atleast_1d(alpha), dtype=np.float32)).cuda()
-    tg.tstgemm(Xd, handle, bd, Yd, alpha=ad)
+    tg.tstgemm(Xd, handle, bd, Yd, alpha=ad, **options)
     torch.cuda.synchronize()
     return Yd.cpu().numpy(), handle
 

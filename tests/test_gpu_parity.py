@@ -157,15 +157,12 @@ def test_launch_shapes(cols_per_wave, k_slices):
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, b)
     h = None
-    try:
-        for slab_tiles in (0, 1, 2):
-            tg.tstgemm_set_tuning(cols_per_wave, k_slices, slab_tiles)
-            Y, h = gpu_tstgemm(W, X, b, handle=h)
-            assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices} slab={slab_tiles}")
-            Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
-            assert np.array_equal(Yi, Ydi.astype(np.float32))
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    for slab_tiles in (0, 1, 2):
+        shape = dict(cols_per_wave=cols_per_wave, k_slices=k_slices, slab_tiles=slab_tiles)
+        Y, h = gpu_tstgemm(W, X, b, handle=h, **shape)
+        assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices} slab={slab_tiles}")
+        Yi, _ = gpu_tstgemm(W, Xi, b, handle=h, **shape)
+        assert np.array_equal(Yi, Ydi.astype(np.float32))
 
 
 @pytest.mark.parametrize("M,K,N,density", [(100, 300, 256, 0.1), (700, 130, 384, 0.03), (300, 200, 200, 0.5),
@@ -179,14 +176,10 @@ def test_eight_columns_per_wavefront(M, K, N, density):
     ot = oracle.tcsc_build(W)
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
-    try:
-        tg.tstgemm_set_tuning(8, 0, 0)
-        Y, h = gpu_tstgemm(W, X, b)
-        assert_close(Y, Yd, A, "8 columns per wavefront")
-        Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h)
-        assert np.array_equal(Yi, Ydi.astype(np.float32))
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    Y, h = gpu_tstgemm(W, X, b, cols_per_wave=8)
+    assert_close(Y, Yd, A, "8 columns per wavefront")
+    Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h, cols_per_wave=8)
+    assert np.array_equal(Yi, Ydi.astype(np.float32))
 
 
 def test_low_density_tall_and_wide_picks_its_own_shape():
@@ -223,14 +216,11 @@ def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density):
     ot = oracle.tcsc_build(W)
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, b)
-    try:
-        tg.tstgemm_set_tuning(cols_per_wave, k_slices, 0)
-        Y, h = gpu_tstgemm(W, X, b)
-        assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices}")
-        Yi, _ = gpu_tstgemm(W, Xi, b, handle=h)
-        assert np.array_equal(Yi, Ydi.astype(np.float32))
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    shape = dict(cols_per_wave=cols_per_wave, k_slices=k_slices)
+    Y, h = gpu_tstgemm(W, X, b, **shape)
+    assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices}")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h, **shape)
+    assert np.array_equal(Yi, Ydi.astype(np.float32))
 
 
 @pytest.mark.parametrize("M,K,N,density", [(40, 40000, 70, 0.25), (64, 300, 20000, 0.5), (20, 70000, 33, 0.0625),
@@ -256,11 +246,9 @@ def test_very_tall_x():
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Y, h = gpu_tstgemm(W, X, b)
     assert_close(Y, Yd, A, f"{M}x{K}x{N}")
-    try:
-        tg.tstgemm_set_tuning(0, 0, 3)      # the same through slabs of three row tiles; K is then sliced, which is
-        Y3, _ = gpu_tstgemm(W, X, b, handle=h)   # another summation order: the oracle is the yardstick again
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    # the same through slabs of three row tiles; K is then sliced, which is another summation order: the oracle is
+    # the yardstick again
+    Y3, _ = gpu_tstgemm(W, X, b, handle=h, slab_tiles=3)
     assert_close(Y3, Yd, A, f"{M}x{K}x{N} in slabs")
 
 
@@ -273,11 +261,7 @@ def test_very_tall_x_wide_columns():
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Y, h = gpu_tstgemm(W, X, b)
     assert_close(Y, Yd, A, f"{M}x{K}x{N}")
-    try:
-        tg.tstgemm_set_tuning(8, 0, 3)
-        Y3, _ = gpu_tstgemm(W, X, b, handle=h)
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    Y3, _ = gpu_tstgemm(W, X, b, handle=h, cols_per_wave=8, slab_tiles=3)
     assert_close(Y3, Yd, A, f"{M}x{K}x{N} in slabs, 8 columns per wavefront")
 
 
@@ -323,13 +307,9 @@ def test_profile_events_bracket_the_main_kernel():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(); e1.record()
     torch.cuda.synchronize()
-    try:
-        tg.tstgemm_profile_events(e0, e1)
-        Y = tg.tstgemm(Xd, t, bd)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-    finally:
-        tg.tstgemm_profile_events(None, None)
+    Y = tg.tstgemm(Xd, t, bd, events=(e0, e1))
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
     assert 0.0 < ms < 50.0
     Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
     assert_close(Y.cpu().numpy(), Yd, A, "C1 with events")
@@ -375,14 +355,10 @@ def test_prelu_in_the_eight_column_shape(per_column):
     a2 = (2.0 ** rng.integers(-3, 3, N)).astype(np.float32) if per_column else np.array([0.5], np.float32)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, bi)
     Ypi, _ = oracle.prelu(Ydi, None, a2)
-    try:
-        tg.tstgemm_set_tuning(8, 0, 0)
-        Y, h = gpu_tstgemm(W, X, b, alpha=alpha)
-        assert_close(Y, Yp, Ap, "prelu, 8 columns per wavefront")
-        Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h, alpha=a2)
-        assert_exact(Yi, Ypi, "prelu integer, 8 columns per wavefront")
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    Y, h = gpu_tstgemm(W, X, b, alpha=alpha, cols_per_wave=8)
+    assert_close(Y, Yp, Ap, "prelu, 8 columns per wavefront")
+    Yi, _ = gpu_tstgemm(W, Xi, bi, handle=h, alpha=a2, cols_per_wave=8)
+    assert_exact(Yi, Ypi, "prelu integer, 8 columns per wavefront")
 
 
 def test_prelu_rejects_bad_slopes():
@@ -451,6 +427,80 @@ def test_calls_can_be_captured_in_a_hip_graph(M):
         assert_close(Yg.cpu().numpy(), Yd, A, f"graph replay {rep}")
 
 
+def test_handles_share_one_workspace_and_streams_run_side_by_side():
+    """Matrices uploaded without a workspace of their own: two of them go through ONE caller-supplied workspace on one
+    stream, call after call, while a third runs on a second stream with a workspace of its own; every result against
+    the oracle, integer inputs bit for bit.  The shapes take the large-M path (with K slices), the small-tile path and
+    the large-M path again."""
+    import torch
+    shapes = [(256, 1024, 512), (40, 2100, 130), (300, 700, 200)]
+    forms = tg.FORM_ROWSETS | tg.FORM_CUTS
+    problems = []
+    for i, (M, K, N) in enumerate(shapes):
+        W, X, b = si.make_inputs(M, K, N, 0.5, "int8" if i == 1 else "normal", seed=880 + i)
+        t = tg.tcsc_upload(tg.tcsc_build(W), forms=forms)
+        assert tg.tcsc_layout(t).workspace_bytes == 0 and tg.tcsc_device_bytes(t) < 8 << 20
+        Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+        problems.append((t, torch.from_numpy(X).cuda(), torch.from_numpy(b).cuda(), Yd, A))
+    need = [tg.tstgemm_workspace_bytes(*s) for s in shapes]
+    shared = torch.empty(max(need[0][1], need[1][1]), dtype=torch.uint8, device="cuda")
+    own = torch.empty(need[2][1], dtype=torch.uint8, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = [[], [], []]
+    for rep in range(3):
+        for i in (0, 1):
+            t, Xd, bd, _, _ = problems[i]
+            outs[i].append(tg.tstgemm(Xd, t, bd, stream=s1, workspace=shared))
+        t, Xd, bd, _, _ = problems[2]
+        outs[2].append(tg.tstgemm(Xd, t, bd, stream=s2, workspace=own))
+    torch.cuda.synchronize()
+    for i, (t, Xd, bd, Yd, A) in enumerate(problems):
+        for Y in outs[i]:
+            if i == 1:
+                assert_exact(Y.cpu().numpy(), Yd, f"problem {i}")
+            else:
+                assert_close(Y.cpu().numpy(), Yd, A, f"problem {i}")
+            assert torch.equal(Y, outs[i][0])
+    # no workspace at all, one below the minimum, a form that was not uploaded
+    t, Xd, bd, _, _ = problems[0]
+    with pytest.raises(tg.TstgemmError) as err:
+        tg.tstgemm(Xd, t, bd)
+    assert err.value.code == -8
+    with pytest.raises(tg.TstgemmError) as err:
+        tg.tstgemm(Xd, t, bd, workspace=shared[:need[0][0] - 256])
+    assert err.value.code == -8
+    with pytest.raises(tg.TstgemmError) as err:
+        tg.tstgemm_signed(Xd[:4].contiguous(), t, bd)
+    assert err.value.code == -7
+    # the minimum is enough (K is then not sliced; another summation order, the oracle decides)
+    Ymin = tg.tstgemm(Xd, t, bd, workspace=shared[:need[0][0]])
+    torch.cuda.synchronize()
+    assert_close(Ymin.cpu().numpy(), problems[0][3], problems[0][4], "minimum workspace")
+
+
+@pytest.mark.parametrize("forms,M,code", [(0, 4, 0), (0, 40, -7), (0, 100, -7), (2, 40, -8), (2 | 32, 40, 0),
+                                          (1 | 32, 100, 0), (1 | 32, 40, -7), (4, 4, 0), (16 | 32, 4, 0)])
+def test_calls_need_their_form(forms, M, code):
+    """tstgemm() on a handle uploaded with a subset of the device forms: the paths whose form (or workspace) is there
+    give the oracle's result, the others an error code and no launch."""
+    import torch
+    K, N = 300, 70
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=890 + M)
+    t = tg.tcsc_upload(tg.tcsc_build(W), forms=forms)
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(b).cuda()
+    fn = tg.tstgemm_packed if forms & 16 else tg.tstgemm
+    if code:
+        with pytest.raises(tg.TstgemmError) as err:
+            fn(Xd, t, bd)
+        assert err.value.code == code
+        return
+    Y = fn(Xd, t, bd)
+    torch.cuda.synchronize()
+    Yd, A, _ = oracle.tstgemm(X, oracle.tcsc_build(W), b)
+    assert_close(Y.cpu().numpy(), Yd, A, f"forms={forms} M={M}")
+
+
 def test_random_shapes_and_densities():
     """Eighty seeded random problems (M, K, N, density, with or without bias, any kernel): real inputs within the
     tolerance, integer inputs bit for bit."""
@@ -495,11 +545,7 @@ def test_decode_list_widths(M, K, N):
     assert tg.tcsc_layout(h).has_lists16 == (1 if K <= 65535 else 0)
     assert_close(Y, Yd, A, f"{M}x{K}x{N}")
     assert np.array_equal(gpu_tstgemm(W, Xi, b, handle=h)[0], Ydi)
-    try:
-        tg.tstgemm_set_decode_lists(True)
-        Yw, _ = gpu_tstgemm(W, X, b, handle=h)
-        Ywi, _ = gpu_tstgemm(W, Xi, b, handle=h)
-    finally:
-        tg.tstgemm_set_decode_lists(False)
+    Yw, _ = gpu_tstgemm(W, X, b, handle=h, wide_lists=True)
+    Ywi, _ = gpu_tstgemm(W, Xi, b, handle=h, wide_lists=True)
     assert_close(Yw, Yd, A, f"{M}x{K}x{N}, 32-bit lists")
     assert np.array_equal(Ywi, Ydi)

@@ -12,14 +12,14 @@ from gpu_util import assert_close, assert_exact
 pytestmark = pytest.mark.gpu
 
 
-def run(fn, W, X, b, handle=None):
+def run(fn, W, X, b, handle=None, **options):
     import torch
     if handle is None:
         handle = tg.tcsc_upload(tg.tcsc_build(W))
     Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
     bd = None if b is None else torch.from_numpy(np.ascontiguousarray(b)).cuda()
     Yd = torch.full((X.shape[0], W.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
-    fn(Xd, handle, bd, Yd)
+    fn(Xd, handle, bd, Yd, **options)
     torch.cuda.synchronize()
     return Yd.cpu().numpy(), handle
 
@@ -115,14 +115,10 @@ def test_packed_k_parts(k_parts, M, K, N):
     _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=561 + M)
     ot = oracle.tcsc_build(W)
     Yd, A = oracle.tstgemm_packed(X, oracle.pack5(W), b, K)
-    try:
-        tg.tstgemm_set_tuning(0, k_parts, 0)
-        Y, h = run(tg.tstgemm_packed, W, X, b)
-        assert_close(Y, Yd, A, f"k_parts={k_parts}")
-        Yi, _ = run(tg.tstgemm_packed, W, Xi, b, handle=h)
-        assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
-    finally:
-        tg.tstgemm_set_tuning(0, 0, 0)
+    Y, h = run(tg.tstgemm_packed, W, X, b, k_slices=k_parts)
+    assert_close(Y, Yd, A, f"k_parts={k_parts}")
+    Yi, _ = run(tg.tstgemm_packed, W, Xi, b, handle=h, k_slices=k_parts)
+    assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
 
 
 def test_variant_degenerate_matrices():

@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
             "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tcsc_signed_arrays", "tcsc_packed_codes",
-            "tstgemm_signed", "tstgemm_packed", "tstgemm_set_tuning", "tstgemm_set_decode_lists",
-            "tstgemm_profile_events", "tcsc_destroy",
+            "tstgemm_signed", "tstgemm_packed", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms",
+            "tstgemm_probe_lds_read", "tstgemm_probe_stream_read", "tcsc_destroy",
             "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
@@ -138,21 +138,88 @@ def test_layout_bookkeeping():
     assert lay.off_signed_index - lay.off_row_index16_neg >= 2 * lay.nnz16_neg
     assert lay.off_packed - lay.off_signed_index >= 4 * (lay.nnz_pos + lay.nnz_neg)
     wide = tg.tcsc_layout(tg.tcsc_build(np.zeros((65536, 1), np.int8)))       # K itself must fit in 16 bits: no copy here
-    assert wide.has_lists16 == 0 and wide.nnz16_pos == 0 and wide.off_row_index16_neg == wide.off_signed_index
+    assert wide.has_lists16 == 0 and wide.nnz16_pos == 0 and wide.off_row_index16_neg == 0
+    assert not wide.forms & tg.FORM_LISTS16
     assert lay.off_workspace - lay.off_packed >= 16 * lay.n_chunks5 * lay.n_pad
     assert lay.total_bytes - lay.off_workspace >= lay.workspace_bytes > 0
 
 
-def test_tuning_rejects_bad_values():
-    lib = ctypes.CDLL(str(tg.library_path()))
-    assert lib.tstgemm_set_tuning(3, 0, 0) == -1
-    assert lib.tstgemm_set_tuning(0, 9, 0) == -1
-    assert lib.tstgemm_set_tuning(0, 0, -1) == -1
-    assert lib.tstgemm_set_tuning(4, 8, 2) == 0
-    assert lib.tstgemm_set_tuning(0, 0, 0) == 0
-    one = ctypes.c_void_p(1)
-    assert lib.tstgemm_profile_events(one, None) == -1
-    assert lib.tstgemm_profile_events(None, None) == 0
+def test_options_reject_bad_values():
+    """tstgemm_ex() checks its options before anything else, so a handle without a device form is enough here (the
+    valid combinations then stop at "not uploaded"); X and Y only have to be non-null."""
+    lib = tg.binding._load()
+    t = tg.tcsc_build(np.zeros((64, 8), np.int8))
+    fake = ctypes.c_void_p(256)
+
+    def call(M=100, **fields):
+        o = tg.binding.TstgemmOpts()
+        o.struct_size = ctypes.sizeof(o)
+        for k, v in fields.items():
+            setattr(o, k, v)
+        return lib.tstgemm_ex(fake, t.handle, None, fake, M, 64, 8, ctypes.byref(o), None)
+
+    assert call() == -3 and lib.tstgemm_ex(fake, t.handle, None, fake, 100, 64, 8, None, None) == -3
+    assert call(struct_size=8) == -1
+    assert call(cols_per_wave=3) == -1 and call(k_slices=9) == -1 and call(k_slices=-1) == -1 and call(slab_tiles=-1) == -1
+    assert call(cols_per_wave=4, k_slices=8, slab_tiles=2) == -3
+    assert call(event_before=1) == -1 and call(event_after=1) == -1 and call(event_before=1, event_after=2) == -3
+    assert call(encoding=3) == -1 and call(encoding=-1) == -1
+    assert call(encoding=1) == -1 and call(M=8, encoding=1) == -3 and call(M=8, encoding=2) == -3   # M <= 8 only
+    assert call(M=8, encoding=1, alpha=256, alpha_count=1) == -1                                   # PReLU: TCSC path only
+    assert call(alpha=256, alpha_count=3) == -1 and call(alpha=256, alpha_count=8) == -3
+    assert call(workspace=100, workspace_bytes=1 << 20) == -1                                      # not 256-byte aligned
+    assert call(workspace=512, workspace_bytes=1 << 20) == -3
+
+
+def test_selected_forms_shrink_the_device_buffer():
+    """A handle only pays for the forms its calls read: the benchmark's smallest configuration with the row sets
+    alone (a caller-supplied workspace) needs under 2 MB, where all forms and the built-in workspace take 160 MiB."""
+    W, _, _ = si.make_workload("C1")
+    t = tg.tcsc_build(W)
+    everything = tg.tcsc_device_bytes(t)
+    assert tg.tcsc_layout(t).forms == tg.FORM_ALL and everything > 160 << 20
+    tg.tcsc_select_forms(t, tg.FORM_ROWSETS)
+    lay = tg.tcsc_layout(t)
+    assert lay.forms == tg.FORM_ROWSETS and tg.tcsc_device_bytes(t) == lay.total_bytes < 2_000_000
+    assert lay.workspace_bytes == 0 and lay.off_list_cuts == 0 and lay.off_signed_index == 0 and lay.off_packed == 0
+    assert lay.has_lists16 == 0 and lay.off_masks > lay.off_row_index_neg > lay.off_row_index_pos > 0
+    tg.tcsc_select_forms(t, tg.FORM_PACKED)                      # the codes are built from the row sets
+    assert tg.tcsc_layout(t).forms == tg.FORM_PACKED | tg.FORM_ROWSETS
+    tg.tcsc_select_forms(t, 0)                                   # the TCSC arrays alone (M <= 8 on 32-bit lists)
+    assert tg.tcsc_layout(t).forms == 0 and tg.tcsc_device_bytes(t) < everything - (160 << 20)
+    with pytest.raises(tg.TstgemmError):
+        tg.tcsc_select_forms(t, 64)
+    tg.tcsc_select_forms(t, tg.FORM_ALL)
+    assert tg.tcsc_device_bytes(t) == everything
+
+
+def test_workspace_bytes():
+    """tstgemm_workspace_bytes: nothing for M <= 8 (but the packed kernel's partial sums), one tile of X as the
+    minimum of the tiled paths, all tiles plus the partial sums of the K slices as the best."""
+    lo, hi = tg.tstgemm_workspace_bytes(1, 4096, 11008)
+    assert lo == 0 and 0 < hi < 16 << 20
+    lo, hi = tg.tstgemm_workspace_bytes(64, 16384, 4096)
+    assert lo == 64 * 16384 * 4 and lo < hi <= lo + 8 * 4096 * 64 * 4
+    assert tg.tstgemm_workspace_bytes(20, 1000, 64)[0] == 32 * 1024 * 4        # tile of 32 rows, K padded to 512-row blocks
+    lo, hi = tg.tstgemm_workspace_bytes(256, 4096, 4096)
+    assert lo == 256 * 4096 * 4 and hi == lo + 8 * 256 * 4096 * 4               # C2: one tile + 8 K slices of Y
+    lo, hi = tg.tstgemm_workspace_bytes(4096, 8192, 8192)
+    assert lo == 256 * 8192 * 4 and hi == 16 * lo                               # C5: 16 tiles, K not sliced
+    assert tg.tstgemm_workspace_bytes(100, 70, 5)[0] == 128 * 128 * 4           # 128-row tile, K padded to 128
+    lib = tg.binding._load()
+    assert lib.tstgemm_workspace_bytes(0, 1, 1, None, None) == -1 and lib.tstgemm_workspace_bytes(1, 1, 1, None, None) == 0
+
+
+def test_too_many_entries_for_the_signed_form():
+    """The inverted-index form numbers the entries of both signs together with 32-bit positions: arrays whose two
+    lists have more than 2^31 - 1 entries together are refused before anything is read."""
+    lib = tg.binding._load()
+    big = np.array([0, 2 ** 30], np.int32)
+    out = ctypes.c_void_p()
+    one = np.zeros(1, np.int32)
+    rc = lib.tcsc_from_arrays(big.ctypes.data, big.ctypes.data, one.ctypes.data, one.ctypes.data, 2 ** 30, 1,
+                              ctypes.byref(out))
+    assert rc == -6 and not out.value
 
 
 @pytest.mark.parametrize("K,N,density", [(1, 1, 1.0), (37, 5, 0.5), (513, 65, 0.5), (64, 9, 1.0), (130, 70, 0.0),
