@@ -39,6 +39,8 @@ extern "C" {
                                      (tcsc_select_forms) */
 #define TSTGEMM_EWORKSPACE (-8)   /* the call needs scratch memory and has none (no workspace argument and none in
                                      the handle), or less than tstgemm_workspace_bytes() gives as the minimum */
+#define TSTGEMM_ESCRATCH (-9)     /* tstgemm_noalloc(): the call needs more scratch memory than the library's static
+                                     buffer (TSTGEMM_NOALLOC_SCRATCH_BYTES) holds */
 
 /* Opaque handle: owns a host copy of the four TCSC arrays; after tcsc_upload() it also
  * remembers (borrows, never frees) the caller's device buffer holding the device form. */
@@ -242,6 +244,22 @@ int tstgemm_ex(const float *X, const tcsc_t *t, const float *b, float *Y, int M,
  */
 int tstgemm_prelu(const float *X, const tcsc_t *t, const float *b, const float *alpha, int alpha_count, float *Y,
                   int M, int K, int N, void *stream);
+
+/*
+ * tstgemm() for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, result and errors as tstgemm_ex()
+ * with default options and a workspace of TSTGEMM_NOALLOC_SCRATCH_BYTES, but the workspace is a static device array
+ * inside the library (one per GPU, held until the process ends), so the handle needs no TCSC_FORM_WORKSPACE and the
+ * call makes no allocation of any kind.  Limit: the minimum of tstgemm_workspace_bytes(M, K, N) must fit the array
+ * (a row tile of 256 rows over K up to 65536; any M -- taller X goes through in slabs, and K is sliced as far
+ * as the rest of the array holds partial sums), else ESCRATCH and nothing is launched.  All calls on one GPU share
+ * that GPU's array: calls that may overlap (different streams without an event between them, different threads)
+ * race on it -- order them, or use tstgemm_ex() with separate workspaces.  The array keeps the last call's contents;
+ * no call depends on them.  The first call on a device looks the array's address up (once per device); make that
+ * call outside a graph capture.
+ */
+#define TSTGEMM_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+int tstgemm_noalloc(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
  * The matrix in the paper's "inverted index" encoding (Sec. 3): one list per column instead of two, +1 in row

@@ -84,6 +84,7 @@ def _load():
     lib.tcsc_destroy.restype = None
     lib.tcsc_strerror.argtypes = [ci]
     lib.tcsc_strerror.restype = ctypes.c_char_p
+    lib.tstgemm_noalloc.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
     lib.tstgemm_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ctypes.POINTER(TstgemmOpts), vp]
     lib.tstgemm_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
     lib.tcsc_select_forms.argtypes = [vp, ctypes.c_uint32]
@@ -93,7 +94,8 @@ def _load():
     lib.tstgemm_probe_stream_read.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_signed", "tstgemm_packed",
-                 "tcsc_signed_arrays", "tcsc_packed_codes", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms"):
+                 "tcsc_signed_arrays", "tcsc_packed_codes", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms",
+                 "tstgemm_noalloc"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -319,6 +321,21 @@ def _variant(name, encoding, X, t, b, Y, stream, options):
         rc = getattr(_load(), name)(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
     if rc != 0:
         raise TstgemmError(rc, name)
+    return Y
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20   # TSTGEMM_NOALLOC_SCRATCH_BYTES of include/tstgemm.h
+
+
+def tstgemm_noalloc(X, t: Tcsc, b, Y, stream=None):
+    """Y = X W + b through the library's static scratch buffer (tstgemm_noalloc of the C ABI).  Y must be given: this
+    wrapper allocates nothing either."""
+    if Y is None:
+        raise ValueError("tstgemm_noalloc needs an output tensor")
+    M, K, N, b_ptr, Y = _gemm_args(X, t, b, Y)
+    rc = _load().tstgemm_noalloc(X.data_ptr(), t.handle, b_ptr, Y.data_ptr(), M, K, N, _stream_ptr(stream))
+    if rc != 0:
+        raise TstgemmError(rc, "tstgemm_noalloc")
     return Y
 
 

@@ -18,7 +18,7 @@ ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libtstgemm.so"
 SOURCES = ["tcsc_host.cpp", "reblock.hip", "tstgemm_side.hip", "tstgemm_large.hip", "tstgemm_small.hip",
-           "tstgemm_decode.hip", "tstgemm_packed.hip", "probes.hip"]
+           "tstgemm_decode.hip", "tstgemm_packed.hip", "probes.hip", "tstgemm_noalloc.hip"]
 ARCH = "gfx950"
 
 

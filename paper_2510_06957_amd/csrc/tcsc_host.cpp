@@ -436,6 +436,7 @@ const char *tcsc_strerror(int code)
     case TSTGEMM_ETOOBIG: return "matrix too large for 32-bit TCSC pointers";
     case TSTGEMM_ENOFORM: return "the device form this call reads was not selected when the matrix was uploaded";
     case TSTGEMM_EWORKSPACE: return "no workspace, or one smaller than tstgemm_workspace_bytes() gives as the minimum";
+    case TSTGEMM_ESCRATCH: return "tstgemm_noalloc: the call needs more scratch memory than the library's static buffer holds";
     default: return "unknown tstgemm error code";
     }
 }
