@@ -155,6 +155,8 @@ def main():
                     help="seconds of the same calls before the warm-up calls, to bring the GPU to its clock")
     ap.add_argument("--repeats", type=int, default=8,
                     help="further timed regions of --steps calls each (events on the launch stream) for the median and minimum")
+    ap.add_argument("--cols-per-wave", type=int, default=0, help="tuning runs: the cols_per_wave option of tstgemm_ex()")
+    ap.add_argument("--k-slices", type=int, default=0, help="tuning runs: the k_slices option of tstgemm_ex()")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured-peak probes (roofline.peak_measured)")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -220,10 +222,12 @@ def main():
     copies = [t] + [tg.tcsc_upload(tg.tcsc_build(W)) for _ in range(n_copies - 1)]
     turn = [0]
 
+    tuning = {k: v for k, v in (("cols_per_wave", args.cols_per_wave), ("k_slices", args.k_slices)) if v}
+
     def gemm_next(**options):
         h = copies[turn[0] % len(copies)]
         turn[0] += 1
-        gemm(Xd, h, bd, Yd, stream, **options)
+        gemm(Xd, h, bd, Yd, stream, **tuning, **options)
 
     if args.traffic_calibration:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")   # 256 MiB read, 256 MiB written per copy
@@ -271,11 +275,11 @@ def main():
     warm_ms = None
     if len(copies) > 1:
         for _ in range(warmup):
-            gemm(Xd, t, bd, Yd, stream)
+            gemm(Xd, t, bd, Yd, stream, **tuning)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(steps):
-            gemm(Xd, t, bd, Yd, stream)
+            gemm(Xd, t, bd, Yd, stream, **tuning)
         e1.record(stream)
         torch.cuda.synchronize()
         warm_ms = e0.elapsed_time(e1) / steps
@@ -384,7 +388,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: M={wl.M} K={wl.K} N={wl.N} density={wl.density} X,b~{wl.dist} "
                                f"seed={wl.seed}", "nnz": nnz, "variant": args.variant, "matrix_copies_in_rotation": len(copies),
-                   "index_bytes_per_call": int(index_bytes),
+                   "index_bytes_per_call": int(index_bytes), "launch_shape_overrides": tuning or None,
                    "preheat_s": args.preheat, "preheat_calls": preheat_calls, "timed_regions": len(region_ms),
                    "spread": "ms_per_step is the wall clock over the first region of `steps` calls; median / min are over "
                              "the time per call of all regions (events on the launch stream)",

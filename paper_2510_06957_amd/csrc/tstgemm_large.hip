@@ -70,55 +70,75 @@ __device__ __forceinline__ int members(u64 set)
 
 // The read phase of a group: COUNT times { k = smallest member of `set`, removed from the set (find-first-set and
 // clear-bit on the scalar unit); address = (k << row_shift) + lane_base (one VALU instruction); ds_read of this lane's R
-// rows of tile row k }.  lane_base is the LDS address of this lane's part of tile row 0.  The empty set yields k = -1
-// and stays empty (the bit cleared is then bit 63): row -1, right in front of the tile, holds zeros.  One asm statement,
-// so that nothing is scheduled or inserted between the instructions; the address register is reused (an LDS
-// instruction takes its address when it is issued).
+// rows of tile row k }.  lane_base is the LDS address of this lane's part of tile row 0.  One asm statement, so that
+// nothing is scheduled or inserted between the instructions; the address register is reused (an LDS instruction takes
+// its address when it is issued).  The set must have at least COUNT members.
 #define TST_READ(i, width) \
     "s_ff1_i32_b64 %[k], %[set]\n\ts_bitset0_b64 %[set], %[k]\n\tv_lshl_add_u32 %[a], %[k], %[sh], %[base]\n\t" \
     "ds_read_" width " %[v" #i "], %[a]\n\t"
-#define TST_READ2(i, j, w) TST_READ(i, w) TST_READ(j, w)
+#define TST_R1(w) TST_READ(0, w)
+#define TST_R2(w) TST_R1(w) TST_READ(1, w)
+#define TST_R3(w) TST_R2(w) TST_READ(2, w)
+#define TST_R4(w) TST_R3(w) TST_READ(3, w)
+#define TST_R5(w) TST_R4(w) TST_READ(4, w)
+#define TST_R6(w) TST_R5(w) TST_READ(5, w)
+#define TST_R7(w) TST_R6(w) TST_READ(6, w)
+#define TST_R8(w) TST_R7(w) TST_READ(7, w)
+// only the value registers a group of COUNT uses are operands, so that a smaller group holds fewer registers
+#define TST_O1 , [v0] "=&v"(v[0])
+#define TST_O2 TST_O1, [v1] "=&v"(v[1])
+#define TST_O3 TST_O2, [v2] "=&v"(v[2])
+#define TST_O4 TST_O3, [v3] "=&v"(v[3])
+#define TST_O5 TST_O4, [v4] "=&v"(v[4])
+#define TST_O6 TST_O5, [v5] "=&v"(v[5])
+#define TST_O7 TST_O6, [v6] "=&v"(v[6])
+#define TST_O8 TST_O7, [v7] "=&v"(v[7])
+#define TST_ASM(reads, outs) \
+    asm volatile(reads : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a) outs : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory")
 template <int R, int COUNT>
 __device__ __forceinline__ void read_rows(typename RowVec<R>::type (&v)[8], int lane_base, u64 &set)
 {
     int k, a;
-    // only the value registers a group of COUNT uses are operands, so that a smaller group holds fewer registers
-#define TST_TAIL : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory"
-#define TST_HEAD : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a), [v0] "=&v"(v[0]), [v1] "=&v"(v[1])
-#define TST_OPERANDS8 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]) TST_TAIL
-#define TST_OPERANDS6 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]) TST_TAIL
-#define TST_OPERANDS4 TST_HEAD, [v2] "=&v"(v[2]), [v3] "=&v"(v[3]) TST_TAIL
-#define TST_OPERANDS2 TST_HEAD TST_TAIL
+    static_assert(COUNT >= 1 && COUNT <= 8, "group sizes");
 #define TST_GROUP(w) \
-    if constexpr (COUNT == 8) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_READ2(6, 7, w) TST_OPERANDS8); \
-    else if constexpr (COUNT == 6) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_READ2(4, 5, w) TST_OPERANDS6); \
-    else if constexpr (COUNT == 4) asm volatile(TST_READ2(0, 1, w) TST_READ2(2, 3, w) TST_OPERANDS4); \
-    else asm volatile(TST_READ2(0, 1, w) TST_OPERANDS2);
-    static_assert(COUNT == 8 || COUNT == 6 || COUNT == 4 || COUNT == 2, "group sizes");
+    if constexpr (COUNT == 8) TST_ASM(TST_R8(w), TST_O8); \
+    else if constexpr (COUNT == 7) TST_ASM(TST_R7(w), TST_O7); \
+    else if constexpr (COUNT == 6) TST_ASM(TST_R6(w), TST_O6); \
+    else if constexpr (COUNT == 5) TST_ASM(TST_R5(w), TST_O5); \
+    else if constexpr (COUNT == 4) TST_ASM(TST_R4(w), TST_O4); \
+    else if constexpr (COUNT == 3) TST_ASM(TST_R3(w), TST_O3); \
+    else if constexpr (COUNT == 2) TST_ASM(TST_R2(w), TST_O2); \
+    else TST_ASM(TST_R1(w), TST_O1);
     if constexpr (R == 4) { TST_GROUP("b128") } else if constexpr (R == 2) { TST_GROUP("b64") } else { TST_GROUP("b32") }
 #undef TST_GROUP
-#undef TST_OPERANDS8
-#undef TST_OPERANDS6
-#undef TST_OPERANDS4
-#undef TST_OPERANDS2
-#undef TST_HEAD
-#undef TST_TAIL
 }
 
-// acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it); when the set has
-// fewer members the rest of the group gathers the row of zeros.  All gathers are issued before the first addition, so
-// COUNT LDS reads are in flight at once; the additions take the values in pairs (second of a pair first), which
-// halves the number of waits.
-// Values I and I + 1 of a group of COUNT: the reads return in order and value I + 1 has COUNT - 2 - I younger reads
-// behind it.  (s_waitcnt immediate of gfx9: vmcnt and expcnt fields all ones = no wait, lgkmcnt in bits 11:8; the
-// scheduling barriers keep the additions of a pair behind its wait.)
-template <int R, bool NEG, int COUNT, int I>
-__device__ __forceinline__ void add_pair(typename RowVec<R>::type &acc, const typename RowVec<R>::type (&v)[8])
+// The reads of a group return in order, so "at most LEFT reads outstanding" means that all but the youngest LEFT have
+// arrived.  The wait is an asm statement that takes the values it makes valid as read-write operands: whatever uses or
+// copies them is data-dependent on the wait and cannot be placed in front of it.  (A scalar load in flight at the same
+// time only makes the wait longer: the counter is the number of LDS reads and scalar loads outstanding together.)
+template <int LEFT, typename V> __device__ __forceinline__ void arrived(V &x, V &y)
 {
-    __builtin_amdgcn_s_waitcnt(0xC07F | ((COUNT - 2 - I) << 8));
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (NEG) { acc -= v[I + 1]; acc -= v[I]; } else { acc += v[I + 1]; acc += v[I]; }
-    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(LEFT));
+}
+template <int LEFT, typename V> __device__ __forceinline__ void arrived(V &x)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(LEFT));
+}
+
+// acc (+/-)= tile[k][rows of this lane] for the COUNT smallest members k of `set` (removed from it).  All gathers are
+// issued before the first addition, so COUNT LDS reads are in flight at once; the additions take the values in pairs
+// (second of a pair first), which halves the number of waits, and a last single one if COUNT is odd.
+template <int R, bool NEG, int COUNT, int I>
+__device__ __forceinline__ void add_arrived(typename RowVec<R>::type &acc, typename RowVec<R>::type (&v)[8])
+{
+    if constexpr (I + 1 < COUNT) {
+        arrived<COUNT - 2 - I>(v[I], v[I + 1]);
+        if constexpr (NEG) { acc -= v[I + 1]; acc -= v[I]; } else { acc += v[I + 1]; acc += v[I]; }
+    } else if constexpr (I < COUNT) {
+        arrived<0>(v[I]);
+        if constexpr (NEG) acc -= v[I]; else acc += v[I];
+    }
 }
 
 template <int R, bool NEG, int COUNT>
@@ -127,31 +147,33 @@ __device__ __forceinline__ void gather(typename RowVec<R>::type &acc, int lane_b
     typedef typename RowVec<R>::type V;
     V v[8];
     read_rows<R, COUNT>(v, lane_base, set);
-    add_pair<R, NEG, COUNT, 0>(acc, v);
-    if constexpr (COUNT > 2) add_pair<R, NEG, COUNT, 2>(acc, v);
-    if constexpr (COUNT > 4) add_pair<R, NEG, COUNT, 4>(acc, v);
-    if constexpr (COUNT > 6) add_pair<R, NEG, COUNT, 6>(acc, v);
+    add_arrived<R, NEG, COUNT, 0>(acc, v);
+    add_arrived<R, NEG, COUNT, 2>(acc, v);
+    add_arrived<R, NEG, COUNT, 4>(acc, v);
+    add_arrived<R, NEG, COUNT, 6>(acc, v);
 }
 
 // One list: every member of the row set is gathered and added to (NEG: subtracted from) acc, in ascending row order,
-// in groups of GMAX = 8 and one last group of 6, 4 or 2 (7 or 8 left over: 8), i.e. with at most one gather of the row
-// of zeros per list.  GMAX = 4 (groups of 4 and a last one of 2): half the registers for values in flight, for the
-// launch shape with eight columns per wavefront, whose lists are short.  The set is wave-uniform.
+// in groups of GMAX and then groups of 4, 2 and 1 for what is left, so that nothing but members of the list is gathered.
+// GMAX = 4: half the registers for values in flight, for the launch shape with eight columns per wavefront, whose
+// lists are short.  The set is wave-uniform.
 template <int R, bool NEG, int GMAX>
 __device__ __forceinline__ void run_list(typename RowVec<R>::type &acc, u64 set, int lane_base)
 {
     static_assert(GMAX == 8 || GMAX == 4, "group sizes");
     int n = members(set);
-    while (n >= GMAX - 1) {
+    while (n >= GMAX) {
         gather<R, NEG, GMAX>(acc, lane_base, set);
         n -= GMAX;
     }
-    // n is now in [-1, GMAX - 2]; independent tests instead of an else-chain keep the accumulators in place
+    // n is now in [0, GMAX): groups of 4, 2 and 1 by the bits of n.  Independent tests instead of an else-chain keep the
+    // accumulators in place (with one group of exactly n behind nested branches the compiler gave the sums different
+    // registers on the paths and copied them: 259 spilled registers in the 4-column kernel).
     if constexpr (GMAX == 8) {
-        if (n >= 5) gather<R, NEG, 6>(acc, lane_base, set);
-        if (n == 3 || n == 4) gather<R, NEG, 4>(acc, lane_base, set);
+        if (n & 4) gather<R, NEG, 4>(acc, lane_base, set);
     }
-    if (n == 1 || n == 2) gather<R, NEG, 2>(acc, lane_base, set);
+    if (n & 2) gather<R, NEG, 2>(acc, lane_base, set);
+    if (n & 1) gather<R, NEG, 1>(acc, lane_base, set);
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -167,6 +189,53 @@ struct LargeArgs {
     int alpha_stride;
 };
 
+// What a workgroup does with its sums: the partial tile of its K slice for k_reduce (the tile as it sits in the
+// registers, [column][row], so that a wavefront stores 64 R contiguous floats per column), or, when K is not sliced,
+// Y = acc + b (bias added once, last), then the optional PReLU.
+template <int R, int NCW>
+__device__ __forceinline__ void finish(const LargeArgs &a, const typename RowVec<R>::type (&acc)[NCW], int mt, int cg,
+                                       int slice, int wave, int lane, int c0)
+{
+    typedef typename RowVec<R>::type V;
+    constexpr int TM = 64 * R;
+    const int M = a.M, N = a.N;
+    const int m0 = mt * TM;
+    if (a.k_slices > 1) {
+        constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
+        float *dst = a.partials + ((size_t)(mt * a.n_colgroups + cg) * a.k_slices + slice) * kTileFloats +
+                     (size_t)(wave * NCW) * TM + lane * R;
+#pragma unroll
+        for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<V *>(dst + (size_t)j * TM));
+        return;
+    }
+    float bias[NCW];
+#pragma unroll
+    for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
+    const bool store_vec = NCW % 4 == 0 && (N % 4 == 0) && (c0 + NCW <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int m = m0 + lane * R + r;
+        if (m >= M) continue;
+        float *yrow = a.Y + (size_t)m * N + c0;
+        if constexpr (NCW % 4 == 0) {
+            if (store_vec) {
+#pragma unroll
+                for (int j0 = 0; j0 < NCW; j0 += 4) {
+                    float4v o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        o[j] = activate(lane_of<R>(acc[j0 + j], r) + bias[j0 + j], a.alpha, a.alpha_stride, c0 + j0 + j);
+                    *reinterpret_cast<float4v *>(yrow + j0) = o;
+                }
+                continue;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NCW; ++j)
+            if (c0 + j < N) yrow[j] = activate(lane_of<R>(acc[j], r) + bias[j], a.alpha, a.alpha_stride, c0 + j);
+    }
+}
+
 // R rows per lane, NCW columns per wavefront, gather groups of at most GMAX.
 template <int R, int NCW, int GMAX>
 __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
@@ -180,7 +249,6 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then tile rows 0 .. 63
     char *const tile = lds + RB;
 
-    const int M = a.M, N = a.N;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
@@ -191,7 +259,6 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     const int cg = wg % a.n_colgroups;
     const int rest = wg / a.n_colgroups;
     const int slice = rest % a.k_slices, mt = rest / a.k_slices;
-    const int m0 = mt * TM;
     const int c0 = (cg * NW + wave) * NCW;   // < n_pad by construction of the grid
     const int kb0 = min(slice * a.kb_per_slice, a.n_kblocks);
     const int kb1 = min(kb0 + a.kb_per_slice, a.n_kblocks);
@@ -252,44 +319,7 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
         }
     }
 
-    // ---- this K slice's partial sums for k_reduce: the tile as it sits in the registers, [column][row], so that a
-    // wavefront stores 64 R contiguous floats per column
-    if (a.k_slices > 1) {
-        constexpr size_t kTileFloats = (size_t)NW * NCW * TM;
-        float *dst = a.partials + ((size_t)(mt * a.n_colgroups + cg) * a.k_slices + slice) * kTileFloats +
-                     (size_t)(wave * NCW) * TM + lane * R;
-#pragma unroll
-        for (int j = 0; j < NCW; ++j) __builtin_nontemporal_store(acc[j], reinterpret_cast<V *>(dst + (size_t)j * TM));
-        return;
-    }
-
-    // ---- output: Y = acc + b (bias added once, last), then the optional PReLU
-    float bias[NCW];
-#pragma unroll
-    for (int j = 0; j < NCW; ++j) bias[j] = (a.b != nullptr && c0 + j < N) ? a.b[c0 + j] : 0.f;
-    const bool store_vec = NCW % 4 == 0 && (N % 4 == 0) && (c0 + NCW <= N) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int m = m0 + lane * R + r;
-        if (m >= M) continue;
-        float *yrow = a.Y + (size_t)m * N + c0;
-        if constexpr (NCW % 4 == 0) {
-            if (store_vec) {
-#pragma unroll
-                for (int j0 = 0; j0 < NCW; j0 += 4) {
-                    float4v o;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        o[j] = activate(lane_of<R>(acc[j0 + j], r) + bias[j0 + j], a.alpha, a.alpha_stride, c0 + j0 + j);
-                    *reinterpret_cast<float4v *>(yrow + j0) = o;
-                }
-                continue;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NCW; ++j)
-            if (c0 + j < N) yrow[j] = activate(lane_of<R>(acc[j], r) + bias[j], a.alpha, a.alpha_stride, c0 + j);
-    }
+    finish<R, NCW>(a, acc, mt, cg, slice, wave, lane, c0);
 }
 
 // One slab: `rows` rows of X (first row X) -> the same rows of Y.  The slab's tiles fit wp.xt.
@@ -313,7 +343,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int r
     a.partials = wp.partials;
     a.M = rows; a.N = l.N; a.n_pad = l.n_pad; a.n_kblocks = l.n_kblocks;
     if constexpr (NCW == 8) {
-        // 128 columns per workgroup: the reduction kernel has no tile of that width, so K is never sliced here
+        // 128 columns per workgroup; K is not sliced in this shape (it is taken when rows x columns fill the chip)
         if (l.n_pad % (NW * NCW) != 0) return hipErrorInvalidValue;
         k_slices = 1;
     }
