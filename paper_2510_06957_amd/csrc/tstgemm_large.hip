@@ -72,7 +72,10 @@ __device__ __forceinline__ int members(u64 set)
 // clear-bit on the scalar unit); address = (k << row_shift) + lane_base (one VALU instruction); ds_read of this lane's R
 // rows of tile row k }.  lane_base is the LDS address of this lane's part of tile row 0.  One asm statement, so that
 // nothing is scheduled or inserted between the instructions; the address register is reused (an LDS instruction takes
-// its address when it is issued).  The set must have at least COUNT members.
+// its address when it is issued).  The set must have at least COUNT members.  While it issues its reads the wavefront
+// runs at a raised priority (s_setprio): the LDS port is the scarcest unit, so a wavefront that has reads to queue goes
+// before the ones that are adding (measured: C2 78.3 -> 75.8 us, C3b 31.6 -> 29.7 us, M = 4096 at 50 % 1.7 % faster;
+// levels 1, 2 and 3 do the same, keeping the priority up between the groups is slower).
 #define TST_READ(i, width) \
     "s_ff1_i32_b64 %[k], %[set]\n\ts_bitset0_b64 %[set], %[k]\n\tv_lshl_add_u32 %[a], %[k], %[sh], %[base]\n\t" \
     "ds_read_" width " %[v" #i "], %[a]\n\t"
@@ -94,7 +97,8 @@ __device__ __forceinline__ int members(u64 set)
 #define TST_O7 TST_O6, [v6] "=&v"(v[6])
 #define TST_O8 TST_O7, [v7] "=&v"(v[7])
 #define TST_ASM(reads, outs) \
-    asm volatile(reads : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a) outs : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory")
+    asm volatile("s_setprio 1\n\t" reads "s_setprio 0\n\t" \
+                 : [set] "+s"(set), [k] "=&s"(k), [a] "=&v"(a) outs : [sh] "n"(row_shift<R>()), [base] "v"(lane_base) : "memory")
 template <int R, int COUNT>
 __device__ __forceinline__ void read_rows(typename RowVec<R>::type (&v)[8], int lane_base, u64 &set)
 {

@@ -87,7 +87,9 @@ __device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *
             for (int t = 0; t < 4; ++t) cur[t] = (4 * g + t < rem) ? cur[t] : k_zero;
         }
         float4v v[4];
+        __builtin_amdgcn_s_setprio(1);   // queueing LDS reads goes before the other wavefronts' additions (about 1 % faster)
         gather4<SH>(v, cur, base);
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if constexpr (NEG) acc -= v[t]; else acc += v[t];
