@@ -36,12 +36,13 @@ PEAK_ALU_INSTR_T = 256 * 64 * 2.4e9 / 1e12     # vector lane-instructions per se
 # script, each counter scaled by what it reads for a copy kernel of known size in the same run.  A counter run cannot
 # be part of a timed run, so these are constants: (bytes, the tracked summary they come from).  Keyed by (workload,
 # variant); workloads without a counter run report null.
-_T_C2 = "profiles/tstgemm_C2_hbm_traffic.md"
+_T_ALL = "profiles/hbm_traffic_all_configs.md"
 _T_OTHER = "profiles/hbm_traffic_other_workloads.md"
 MEASURED_TRAFFIC = {
-    ("C2", "tcsc"): (46333133, _T_C2), ("C5a", "tcsc"): (931596902, _T_OTHER),
+    ("C1", "tcsc"): (1790175, _T_ALL), ("C2", "tcsc"): (46315585, _T_ALL), ("C3a", "tcsc"): (46375291, _T_ALL),
+    ("C3b", "tcsc"): (46398868, _T_ALL), ("C4-1", "tcsc"): (46061287, _T_ALL), ("C4-8", "tcsc"): (47344285, _T_ALL),
+    ("C5a", "tcsc"): (929269408, _T_ALL), ("C5b", "tcsc"): (922772760, _T_ALL), ("C5c", "tcsc"): (902895935, _T_ALL),
     ("M64-K16384-N4096-d0.5", "tcsc"): (167681434, _T_OTHER),
-    ("C4-1", "tcsc"): (46066176, _T_OTHER), ("C4-8", "tcsc"): (47349248, _T_OTHER),
     ("C4-1", "packed"): (9611264, _T_OTHER), ("C4-8", "packed"): (11882291, _T_OTHER),
 }
 ORACLE_FLAGS = "gcc -O3 -fstrict-aliasing -DNDEBUG -fopenmp (the paper's flags, Sec. 4, without -march=native)"
@@ -57,18 +58,6 @@ def cpu_baseline(W, X, b, nnz, variant="tcsc", budget_s=10.0):
     rows = None
     if M * nnz > 4e10:   # keep the sample to seconds: a slice of rows (the cost per row does not depend on M)
         rows = np.arange(0, M, M // 64, dtype=np.int32)[:64]
-    one = None
-    if variant == "tcsc":
-        # one thread: as many evenly spaced rows as take about a tenth of a second each time, for about 3 s
-        n1 = int(max(1, min(M, 2e8 // max(nnz, 1))))
-        rows1 = np.arange(0, M, max(1, M // n1), dtype=np.int32)[:n1]
-        t1, t_start = [], time.perf_counter()
-        while len(t1) < 3 or (time.perf_counter() - t_start < 3.0 and len(t1) < 50):
-            t0 = time.perf_counter()
-            _, _, used1 = oracle.tstgemm(X, t, b, rows=rows1, threads=1)
-            t1.append(time.perf_counter() - t0)
-        one = {"value": len(rows1) * nnz / min(t1) / 1e9, "unit": "Gadds/s", "cores": int(used1),
-               "sample": f"{len(rows1)} of {M} rows, evenly spaced, best of {len(t1)}"}
     if variant == "signed":
         enc = oracle.signed_build(t)
     elif variant == "packed":
@@ -85,6 +74,19 @@ def cpu_baseline(W, X, b, nnz, variant="tcsc", budget_s=10.0):
         else:
             _, _, used = oracle.tstgemm(X, t, b) if rows is None else oracle.tstgemm(X, t, b, rows=rows)
         times.append(time.perf_counter() - t0)
+    # (after the all-core run: the oracle's thread count, once set, stays set for later calls)
+    one = None
+    if variant == "tcsc":
+        # one thread: as many evenly spaced rows as take about a tenth of a second each time, for about 3 s
+        n1 = int(max(1, min(M, 2e8 // max(nnz, 1))))
+        rows1 = np.arange(0, M, max(1, M // n1), dtype=np.int32)[:n1]
+        t1, t_start = [], time.perf_counter()
+        while len(t1) < 3 or (time.perf_counter() - t_start < 3.0 and len(t1) < 50):
+            t0 = time.perf_counter()
+            _, _, used1 = oracle.tstgemm(X, t, b, rows=rows1, threads=1)
+            t1.append(time.perf_counter() - t0)
+        one = {"value": len(rows1) * nnz / min(t1) / 1e9, "unit": "Gadds/s", "cores": int(used1),
+               "sample": f"{len(rows1)} of {M} rows, evenly spaced, best of {len(t1)}"}
     mean = float(np.mean(times))
     m_used = M if rows is None else len(rows)
     out = {"value": m_used * nnz / mean / 1e9, "unit": "Gadds/s", "cores": int(used), "kind": "oracle",
@@ -355,8 +357,8 @@ def main():
     hbm_bytes = traffic if traffic is not None else alg_bytes
     roof["hbm_gb_per_s"] = hbm_bytes / (kernel_ms * 1e-3) / 1e9
     roof["hbm_frac"] = roof["hbm_gb_per_s"] / PEAK_HBM_GBS
-    roof["hbm_bytes_are"] = (f"constant from {measured[1]} (rocprofv3 --pmc runs of this script on an earlier build of the "
-                             "kernel, not re-measured in this run)" if measured else "algorithmic")
+    roof["hbm_bytes_are"] = (f"constant from {measured[1]} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script; a counter "
+                             "run cannot be part of a timed run, so not re-measured here)" if measured else "algorithmic")
     roof["algorithmic_adds_per_launch"] = adds
     roof["algorithmic_bytes_per_launch"] = alg_bytes
     # the same accounting for the whole call (packing pre-pass + main kernel + split-K reduction)

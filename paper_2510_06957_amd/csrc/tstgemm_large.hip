@@ -14,18 +14,19 @@
 //     all TM rows (the paper's "vertical" SIMD scheme and its M-unrolling, Sec. 3, carried to
 //     64 lanes); the gather of one index is a single conflict-free ds_read (b32/b64/b128);
 //   * K is cut into blocks of 64 (the paper's blocking idea, Sec. 3 "Blocking"); a workgroup
-//     (16 wavefronts = 16 NCW columns) keeps one K-block of its tile in the LDS, in front of it
-//     a row of zeros;
+//     (16 wavefronts = 16 NCW columns) keeps one K-block of its tile in the LDS;
 //   * a list piece (one column, one K-block, one sign) arrives as a 64-bit row set, fetched by
 //     the scalar unit; the scalar unit turns it into row numbers with find-first-set /
 //     clear-bit, so an index costs two SALU instructions and neither VALU work, LDS traffic nor
-//     memory latency.  An exhausted set yields row -1, the row of zeros: pieces are padded to
-//     an even number of gathers that way (the paper pads its interleaved groups with a dummy
-//     zero index for the same reason, Sec. 3), which leaves four group sizes: 8, 6, 4 and 2;
-//   * the gathers of a group are all issued before the first addition; the latency of a group
-//     is covered by the other wavefronts: the kernel is built for 8 wavefronts per SIMD (at
-//     most 64 VGPRs, two workgroups per compute unit).  While one workgroup exchanges its tile
-//     between two barriers, the other one computes;
+//     memory latency.  A piece is walked in groups of 8 gathers (4 in the shape with 8 columns per
+//     wavefront) and then groups of 4, 2 and 1 for what is left: nothing but members of the list is
+//     gathered (the paper pads its interleaved groups with a dummy zero index, Sec. 3; here a
+//     padded gather costs as many vector instructions as a real one, and those are what the kernel
+//     is bound by);
+//   * the gathers of a group are all issued before the first addition, at a raised wavefront
+//     priority; the latency of a group is covered by the other wavefronts: the kernel is built for
+//     8 wavefronts per SIMD (at most 64 VGPRs, two workgroups per compute unit).  While one
+//     workgroup exchanges its tile between two barriers, the other one computes;
 //   * accumulators stay in VGPRs over all K-blocks of the workgroup's K slice; the bias add and
 //     the store are fused;
 //   * when rows x columns alone give too few workgroups to fill the chip, K is cut into up to
@@ -250,8 +251,7 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
     constexpr int STAGE = kKBlock * RB;        // bytes of one K-block of the tile
     constexpr int LPT = STAGE / (NT * 16);     // 16-byte pieces per thread and K-block
     static_assert(LPT >= 1 && STAGE % (NT * 16) == 0, "staging layout");
-    __shared__ __attribute__((aligned(16))) char lds[RB + STAGE];   // the row of zeros, then tile rows 0 .. 63
-    char *const tile = lds + RB;
+    __shared__ __attribute__((aligned(16))) char tile[STAGE];   // tile rows 0 .. 63 of the current K-block
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -295,13 +295,12 @@ __global__ void __launch_bounds__(NT, 8) k_large(const LargeArgs a)
             for (int i = 0; i < 2 * NCW; ++i) sets[i] = sets_base[(size_t)kb * sets_stride + i];
         };
 
-        if (threadIdx.x < RB / 4) reinterpret_cast<float *>(lds)[threadIdx.x] = 0.f;
         load_sets(kb0);
         stage_load(kb0);
         stage_store();
         __syncthreads();
         // LDS address of this lane's rows in tile row 0 (the asm reads take plain LDS addresses)
-        const int lane_base = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds + RB + lane * (R * 4);
+        const int lane_base = (int)(uintptr_t)(__attribute__((address_space(3))) char *)tile + lane * (R * 4);
         for (int kb = kb0; kb < kb1; ++kb) {
 #pragma unroll
             for (int j = 0; j < NCW; ++j) {
