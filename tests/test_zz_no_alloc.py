@@ -56,6 +56,40 @@ def test_noalloc_in_slabs():
     assert_close(Y1, Yd, A, "noalloc in slabs")
 
 
+def test_noalloc_under_graph_capture():
+    """What the entry point is for: a stream capture records it (kernels only, nothing allocated, the array's address
+    looked up by the call before the capture); every replay, with new contents of X and eager work in between, gives
+    the eager result bit for bit."""
+    import torch
+    M, K, N = 256, 1024, 512
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=997)
+    t = tg.tcsc_upload(tg.tcsc_build(W), forms=tg.FORM_ROWSETS)
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(b).cuda()
+    Yg = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    Ye = torch.empty_like(Yg)
+    tg.tstgemm_noalloc(Xd, t, bd, Yg)              # first call on the device: outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tg.tstgemm_noalloc(Xd, t, bd, Yg, stream=side)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(998)
+    for rep in range(3):
+        Xn = rng.standard_normal((M, K)).astype(np.float32)
+        Xd.copy_(torch.from_numpy(Xn).cuda())
+        Yg.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        tg.tstgemm_noalloc(Xd, t, bd, Ye)
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, Ye), f"replay {rep}"
+        Yd, A, _ = oracle.tstgemm(Xn, oracle.tcsc_build(W), b)
+        assert_close(Yg.cpu().numpy(), Yd, A, f"noalloc graph replay {rep}")
+
+
 def test_noalloc_rejects_what_does_not_fit():
     """One row tile over K must fit the static array: K = 200000 at M = 100 needs 128 x 200000 x 4 bytes."""
     import torch
