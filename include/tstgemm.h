@@ -100,6 +100,10 @@ int tcsc_device_bytes(const tcsc_t *t, size_t *bytes);
  *                                             8 entries (16 bytes) with the value K, which stands for a row of zeros;
  *                                             col_start16 are the pointers into these padded arrays.  Half the bytes for
  *                                             the small-M kernel, which is bound by them, and no partly used 16-byte piece.
+ *                                             Inside a column's list the entries are NOT ascending: their order (a sum
+ *                                             does not care) is chosen so that the sixteen lanes that gather together get
+ *                                             rows that differ modulo 16, i.e. lie in different LDS banks; the pad entries
+ *                                             can be anywhere in the list.
  *   signed_index int32 [nnz_pos + nnz_neg]    the "inverted index" form (Sec. 3): the two lists of a column merged in
  *                                             ascending row order, +1 in row i stored as i, -1 as ~i; column n's
  *                                             entries are [col_start_pos[n] + col_start_neg[n],

@@ -97,23 +97,6 @@ k_merge_signed(const int32_t *__restrict__ cs_own, const int32_t *__restrict__ c
     merged[cs_own[n] + cs_other[n] + (i - cs_own[n]) + smaller] = SIGN ? ~row : row;
 }
 
-// Padded 16-bit copy of a row_index array: one thread per destination entry; entries behind the end of a column's
-// list (at most 7, up to the next multiple of 8) get the value K, the row of zeros of the small-M kernel.
-__global__ void __launch_bounds__(kThreads)
-k_lists16(const int32_t *__restrict__ cs, const int32_t *__restrict__ cs16, const int32_t *__restrict__ rows,
-          uint16_t *__restrict__ rows16, int N, int nnz16, int K)
-{
-    const int j = blockIdx.x * kThreads + threadIdx.x;
-    if (j >= nnz16) return;
-    int lo = 0, hi = N;   // the column of entry j: the last n with cs16[n] <= j
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (cs16[mid] <= j) lo = mid; else hi = mid;
-    }
-    const int local = j - cs16[lo], len = cs[lo + 1] - cs[lo];
-    rows16[j] = (uint16_t)(local < len ? rows[cs[lo] + local] : K);
-}
-
 // Value compression (Sec. 3 of the paper): five consecutive rows of a column as one base-3 number, digit 0 / 1 / 2 for
 // an entry 0 / +1 / -1, first row most significant.  One thread per (chunk of 16 groups, column) reads the 80 rows
 // from the row sets and stores its 16 bytes at once.
@@ -181,15 +164,6 @@ hipError_t launch_reblock(const tcsc *t, hipStream_t stream)
                            stream, d.col_start_neg, d.col_start_pos, d.row_index_neg, d.row_index_pos, d.signed_index, l.N,
                            (int)l.nnz_neg);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (l.has_lists16) {
-        if (l.nnz16_pos > 0)
-            hipLaunchKernelGGL(k_lists16, dim3((unsigned)((l.nnz16_pos + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
-                               d.col_start_pos, d.col_start16_pos, d.row_index_pos, d.row_index16_pos, l.N, (int)l.nnz16_pos, l.K);
-        if (l.nnz16_neg > 0)
-            hipLaunchKernelGGL(k_lists16, dim3((unsigned)((l.nnz16_neg + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
-                               d.col_start_neg, d.col_start16_neg, d.row_index_neg, d.row_index16_neg, l.N, (int)l.nnz16_neg, l.K);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
     if (!(l.forms & TCSC_FORM_PACKED)) return hipSuccess;
     const long long pack_cells = (long long)l.n_pad * l.n_chunks5;
     hipLaunchKernelGGL(k_pack5, dim3((unsigned)((pack_cells + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,

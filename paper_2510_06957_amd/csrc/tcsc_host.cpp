@@ -79,6 +79,45 @@ void compute_layout(tcsc *t)
     l.forms = forms;
 }
 
+// The padded 16-bit copy of one sign's lists for the small-M kernel (M <= 8, all of X in the LDS): column n's list at
+// [cs16[n], cs16[n + 1]), a multiple of 8 entries, pad value K (the row of zeros).  The kernel deals a list to the
+// wavefront in rounds of 512 entries: lane l takes the 8 consecutive entries 8 l .. 8 l + 7 of a round and gathers,
+// for each of its 8 slots in turn, the row of X in the LDS (16 bytes per plane of four rows of X).  Sixteen consecutive
+// lanes gather together, and rows that are equal modulo 16 lie in the same LDS banks: in ascending order (random rows)
+// half of the LDS time of M = 8 went into bank conflicts.  The order inside a column's list is free (a sum), so it is
+// chosen here: the t-th entry with row = c mod 16 goes to member c of the t-th group of 16 lanes x one slot, which makes
+// the sixteen rows of a group different modulo 16; entries of a class that has more members than there are whole
+// groups go, in order, to the positions that stayed free, and what is then still free is padding.
+void build_lists16(const std::vector<int32_t> &cs, const std::vector<int32_t> &rows, const std::vector<int32_t> &cs16, int N,
+                   int K, std::vector<uint16_t> &out)
+{
+    const uint16_t pad = (uint16_t)K;
+    out.assign((size_t)cs16[N] + tst::kIndexSlack, pad);
+    std::vector<int32_t> overflow;
+    for (int n = 0; n < N; ++n) {
+        const int32_t *col = rows.data() + cs[n];
+        const int len = cs[n + 1] - cs[n], len16 = cs16[n + 1] - cs16[n];
+        uint16_t *dst = out.data() + cs16[n];
+        // whole groups: 4 x 8 per whole round of 512, then 8 per 16 whole lanes of the last round
+        const int whole_rounds = len16 / 512, last_lanes = (len16 % 512) / 8;
+        const int groups = whole_rounds * 32 + (last_lanes / 16) * 8;
+        int members[16] = {0};
+        overflow.clear();
+        for (int i = 0; i < len; ++i) {
+            const int c = col[i] & 15, t = members[c]++;
+            if (t < groups) {
+                const int r = t / 32, j = (t % 32) / 8, e = t % 8;   // group t: round r, lanes 16 j .. 16 j + 15, slot e
+                dst[r * 512 + (16 * j + c) * 8 + e] = (uint16_t)col[i];
+            } else {
+                overflow.push_back(col[i]);
+            }
+        }
+        size_t next = 0;
+        for (int p = 0; p < len16 && next < overflow.size(); ++p)
+            if (dst[p] == pad) dst[p] = (uint16_t)overflow[next++];
+    }
+}
+
 // The structural rules of the format: monotone pointers starting at 0, rows inside [0,K),
 // strictly ascending inside a column, no row in both lists of a column.
 int validate(const int32_t *csp, const int32_t *csn, const int32_t *rip, const int32_t *rin, int K, int N)
@@ -309,9 +348,21 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream)
     if (copy(l.off_col_start_neg, t->col_start_neg) != hipSuccess) return TSTGEMM_EHIP;
     if (copy(l.off_row_index_pos, t->row_index_pos) != hipSuccess) return TSTGEMM_EHIP;
     if (copy(l.off_row_index_neg, t->row_index_neg) != hipSuccess) return TSTGEMM_EHIP;
+    std::vector<uint16_t> lists16_pos, lists16_neg;   // must outlive the copies: freed behind the synchronisation below
     if (l.has_lists16) {
         if (copy(l.off_col_start16_pos, t->col_start16_pos) != hipSuccess) return TSTGEMM_EHIP;
         if (copy(l.off_col_start16_neg, t->col_start16_neg) != hipSuccess) return TSTGEMM_EHIP;
+        try {
+            build_lists16(t->col_start_pos, t->row_index_pos, t->col_start16_pos, t->N, t->K, lists16_pos);
+            build_lists16(t->col_start_neg, t->row_index_neg, t->col_start16_neg, t->N, t->K, lists16_neg);
+        } catch (const std::bad_alloc &) {
+            return TSTGEMM_ENOMEM;
+        }
+        if (hipMemcpyAsync(d + l.off_row_index16_pos, lists16_pos.data(), lists16_pos.size() * sizeof(uint16_t),
+                           hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(d + l.off_row_index16_neg, lists16_neg.data(), lists16_neg.size() * sizeof(uint16_t),
+                           hipMemcpyHostToDevice, s) != hipSuccess)
+            return TSTGEMM_EHIP;
     }
     // The sources are pageable host memory: wait until the copies have read them.
     if (hipStreamSynchronize(s) != hipSuccess) return TSTGEMM_EHIP;

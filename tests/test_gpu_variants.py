@@ -53,7 +53,8 @@ def test_device_forms_match_the_oracle(K, N, density):
             col = ri[cs[n]:cs[n + 1]]
             got = ri16[cs16[n]:cs16[n + 1]]
             assert got.size == -(-col.size // 8) * 8
-            assert np.array_equal(got[:col.size], col) and np.all(got[col.size:] == K)
+            # the order inside a list is the library's (chosen for the LDS banks): the same rows, each once, and the pad
+            assert np.array_equal(np.sort(got[got != K]), col) and np.count_nonzero(got == K) == got.size - col.size
     # packed[chunk][column][16]: group g of column n is byte [g // 16][n][g % 16]; padding groups and columns are 0
     dev = device_section(t, lay.off_packed, lay.n_chunks5 * lay.n_pad * 16, np.uint8).reshape(lay.n_chunks5, lay.n_pad, 16)
     codes = oracle.pack5(W)                                       # [N][G]
@@ -119,6 +120,30 @@ def test_packed_k_parts(k_parts, M, K, N):
     assert_close(Y, Yd, A, f"k_parts={k_parts}")
     Yi, _ = run(tg.tstgemm_packed, W, Xi, b, handle=h, k_slices=k_parts)
     assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+
+
+def test_lists16_order_spreads_rows_over_the_bank_groups():
+    """The padded 16-bit lists are stored so that the sixteen lanes that gather together (lanes 16 j .. 16 j + 15 of a
+    round of 512 entries, same slot of their 8) get rows that differ modulo 16: on a benchmark-sized random column most
+    whole groups must be free of repeats (a class of rows with fewer members than there are groups leaves holes that other
+    classes fill: about one group in eight has one repeat; in ascending order about one group in a thousand has none)."""
+    K, N = 4096, 24
+    W, _, _ = si.make_inputs(1, K, N, 0.5, "uniform", seed=470)
+    t = tg.tcsc_upload(tg.tcsc_build(W))
+    lay = tg.tcsc_layout(t)
+    cs16 = device_section(t, lay.off_col_start16_pos, N + 1, np.int32)
+    ri16 = device_section(t, lay.off_row_index16_pos, lay.nnz16_pos, np.uint16)
+    whole = clean = 0
+    for n in range(N):
+        col = ri16[cs16[n]:cs16[n + 1]].astype(np.int64)
+        for r in range(col.size // 512):
+            rnd = col[r * 512:(r + 1) * 512].reshape(64, 8)            # [lane][slot]
+            for j in range(4):
+                for e in range(8):
+                    rows = rnd[16 * j:16 * j + 16, e]
+                    whole += 1
+                    clean += np.unique(rows % 16).size == 16 and not (rows == K).any()
+    assert whole >= N * 8 and clean >= 0.8 * whole, (clean, whole)
 
 
 def test_variant_degenerate_matrices():
