@@ -123,14 +123,24 @@ __device__ __forceinline__ void run_list16(float (&acc)[MM], const uint16_t *__r
         const uint4v q = ahead;
         ahead = fetch(at + 512);   // the next round is on its way while this one is gathered
         if (at + lane * 8 < p1) {
+            // four entries at a time: all their gathers are issued before the first addition (left to itself the
+            // compiler waits for the two reads of an entry right behind them, one entry in flight per wavefront)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int row = (int)((q[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+            for (int e0 = 0; e0 < 8; e0 += 4) {
+                float x[4][MM];
 #pragma unroll
-                for (int m = 0; m < MM; ++m) {
-                    const float x = xs[xs_at<MM>(row, m, kc1)];
-                    if (NEG) acc[m] -= x; else acc[m] += x;
+                for (int e = 0; e < 4; ++e) {
+                    const int row = (int)((q[(e0 + e) >> 1] >> (16 * (e & 1))) & 0xffffu);
+#pragma unroll
+                    for (int m = 0; m < MM; ++m) x[e][m] = xs[xs_at<MM>(row, m, kc1)];
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int m = 0; m < MM; ++m) {
+                        if (NEG) acc[m] -= x[e][m]; else acc[m] += x[e][m];
+                    }
             }
         }
     }
