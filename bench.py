@@ -159,6 +159,8 @@ def main():
                     help="further timed regions of --steps calls each (events on the launch stream) for the median and minimum")
     ap.add_argument("--cols-per-wave", type=int, default=0, help="tuning runs: the cols_per_wave option of tstgemm_ex()")
     ap.add_argument("--k-slices", type=int, default=0, help="tuning runs: the k_slices option of tstgemm_ex()")
+    ap.add_argument("--wide-lists", action="store_true",
+                    help="M <= 8: the decode_wide_lists option of tstgemm_ex() (the 32-bit TCSC lists instead of their 16-bit copy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured-peak probes (roofline.peak_measured)")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -203,7 +205,7 @@ def main():
     decode = wl.M <= 8          # the library's rules for its decode kernel ...
     small = 8 < wl.M <= 64      # ... and its small-tile kernel
     # index data one call reads (what must not be in the Infinity Cache for an HBM figure)
-    narrow = (decode and args.variant == "tcsc" and bool(lay.has_lists16)
+    narrow = (decode and args.variant == "tcsc" and bool(lay.has_lists16) and not args.wide_lists
               and wl.K <= 150 * 1024 // (4 * wl.M) - 1)   # the library's rule for its padded 16-bit lists
     if args.variant == "packed":
         index_bytes = lay.n_chunks5 * lay.n_pad * 16
@@ -224,7 +226,8 @@ def main():
     copies = [t] + [tg.tcsc_upload(tg.tcsc_build(W)) for _ in range(n_copies - 1)]
     turn = [0]
 
-    tuning = {k: v for k, v in (("cols_per_wave", args.cols_per_wave), ("k_slices", args.k_slices)) if v}
+    tuning = {k: v for k, v in (("cols_per_wave", args.cols_per_wave), ("k_slices", args.k_slices),
+                                ("wide_lists", args.wide_lists)) if v}
 
     def gemm_next(**options):
         h = copies[turn[0] % len(copies)]
