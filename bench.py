@@ -159,6 +159,7 @@ def main():
                     help="further timed regions of --steps calls each (events on the launch stream) for the median and minimum")
     ap.add_argument("--cols-per-wave", type=int, default=0, help="tuning runs: the cols_per_wave option of tstgemm_ex()")
     ap.add_argument("--k-slices", type=int, default=0, help="tuning runs: the k_slices option of tstgemm_ex()")
+    ap.add_argument("--list-walk", type=int, default=0, help="tuning runs: the list_walk option of tstgemm_ex() (8 < M <= 64)")
     ap.add_argument("--wide-lists", action="store_true",
                     help="M <= 8: the decode_wide_lists option of tstgemm_ex() (the 32-bit TCSC lists instead of their 16-bit copy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -227,7 +228,7 @@ def main():
     turn = [0]
 
     tuning = {k: v for k, v in (("cols_per_wave", args.cols_per_wave), ("k_slices", args.k_slices),
-                                ("wide_lists", args.wide_lists)) if v}
+                                ("wide_lists", args.wide_lists), ("list_walk", args.list_walk)) if v}
 
     def gemm_next(**options):
         h = copies[turn[0] % len(copies)]

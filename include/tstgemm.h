@@ -218,6 +218,10 @@ typedef struct tstgemm_opts {
      * k_slices: 1..8 slices of K computed by different workgroups and summed in slice order (also the workgroups per
      * column group of encoding 2); slab_tiles: at most this many row tiles of X packed and processed at a time. */
     int cols_per_wave, k_slices, slab_tiles;
+    int list_walk;           /* 8 < M <= 64, for tuning runs and tests: 0 = the built-in choice by the density of W,
+                                1 = the plain walk of the lists (best on short lists), 2 = the walk that requests the
+                                entries of a list two steps ahead (best from about 40 entries per list and 256 rows of
+                                W on).  Same sums, added in a different order */
     int decode_wide_lists;   /* != 0: M <= 8 reads the 32-bit TCSC lists even where the padded 16-bit copy exists.  The two
                                 deal the entries of a list to the lanes differently, so fp32 rounding can differ in the
                                 last bits; integer-valued inputs give the same, exact result */

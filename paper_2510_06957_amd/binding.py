@@ -41,7 +41,7 @@ class TstgemmOpts(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_size_t), ("encoding", ctypes.c_int), ("alpha_count", ctypes.c_int),
                 ("alpha", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("cols_per_wave", ctypes.c_int), ("k_slices", ctypes.c_int), ("slab_tiles", ctypes.c_int),
-                ("decode_wide_lists", ctypes.c_int), ("event_before", ctypes.c_void_p), ("event_after", ctypes.c_void_p)]
+                ("list_walk", ctypes.c_int), ("decode_wide_lists", ctypes.c_int), ("event_before", ctypes.c_void_p), ("event_after", ctypes.c_void_p)]
 
 
 # TCSC_FORM_* of include/tstgemm.h
@@ -264,13 +264,13 @@ def _gemm_args(X, t: Tcsc, b, Y):
 
 
 def _opts(X, N, encoding=0, alpha=None, workspace=None, cols_per_wave=0, k_slices=0, slab_tiles=0, wide_lists=False,
-          events=None):
+          events=None, list_walk=0):
     """tstgemm_opts_t from keyword arguments, or None when every one has its default (argument marshalling only).
     workspace: a CUDA tensor on X's device; events: a pair of torch.cuda.Event(enable_timing=True) objects that have
     been recorded once (so that their native handles exist)."""
     import torch
     if (encoding == 0 and alpha is None and workspace is None and not cols_per_wave and not k_slices and not slab_tiles
-            and not wide_lists and events is None):
+            and not wide_lists and events is None and not list_walk):
         return None
     o = TstgemmOpts()
     o.struct_size = ctypes.sizeof(TstgemmOpts)
@@ -285,6 +285,7 @@ def _opts(X, N, encoding=0, alpha=None, workspace=None, cols_per_wave=0, k_slice
             raise ValueError("workspace must be a contiguous CUDA tensor on X's device")
         o.workspace, o.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     o.cols_per_wave, o.k_slices, o.slab_tiles = int(cols_per_wave), int(k_slices), int(slab_tiles)
+    o.list_walk = int(list_walk)
     o.decode_wide_lists = int(bool(wide_lists))
     if events is not None:
         o.event_before, o.event_after = events[0].cuda_event, events[1].cuda_event
@@ -294,7 +295,7 @@ def _opts(X, N, encoding=0, alpha=None, workspace=None, cols_per_wave=0, k_slice
 def tstgemm(X, t: Tcsc, b=None, Y=None, stream=None, alpha=None, **options):
     """Y = X W + b on the GPU, or Y = PReLU(X W + b) when `alpha` is given (tstgemm_prelu of the C ABI).
     X: cuda float32 [M, K] contiguous; b: cuda float32 [N] or None; alpha: cuda float32 with 1 or N entries.
-    options (tstgemm_ex of the C ABI): workspace=, cols_per_wave=, k_slices=, slab_tiles=, wide_lists=, events=.
+    options (tstgemm_ex of the C ABI): workspace=, cols_per_wave=, k_slices=, slab_tiles=, list_walk=, wide_lists=, events=.
 
     Launches on `stream` (default: torch's current stream) of the current device, which must be the device the
     handle was uploaded to and the one holding X, b, alpha and Y."""

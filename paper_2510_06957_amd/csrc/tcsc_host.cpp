@@ -321,6 +321,13 @@ int tstgemm_workspace_bytes(int M, int K, int N, size_t *min_bytes, size_t *best
         lo = tst::small_tile_bytes(M, K);
         const size_t n_pad = ((size_t)N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
         hi = align_up(lo) + (size_t)tst::kMaxKSlices * n_pad * (M <= 32 ? 32 : 64) * sizeof(float);
+        if ((long long)K * N >= (1LL << 30)) {
+            // a matrix of this size can have lists too long for the small-tile kernel; then the large-M kernel runs
+            size_t lo_large = 0, hi_large = 0;
+            tst::large_workspace_bytes(M, K, (int)n_pad, &lo_large, &hi_large);
+            lo = lo > lo_large ? lo : lo_large;
+            hi = hi > hi_large ? hi : hi_large;
+        }
     } else {
         const int n_pad = (N + tst::kColPad - 1) / tst::kColPad * tst::kColPad;
         tst::large_workspace_bytes(M, K, n_pad, &lo, &hi);
@@ -385,6 +392,7 @@ int run(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K,
     if (o.cols_per_wave != 0 && o.cols_per_wave != 1 && o.cols_per_wave != 2 && o.cols_per_wave != 4 && o.cols_per_wave != 8)
         return TSTGEMM_EINVAL;
     if (o.k_slices < 0 || o.k_slices > tst::kMaxKSlices || o.slab_tiles < 0) return TSTGEMM_EINVAL;
+    if (o.list_walk < 0 || o.list_walk > 2) return TSTGEMM_EINVAL;
     if ((o.event_before == nullptr) != (o.event_after == nullptr)) return TSTGEMM_EINVAL;
     if (o.workspace && reinterpret_cast<uintptr_t>(o.workspace) % kAlign) return TSTGEMM_EINVAL;
     if (!t->uploaded) return TSTGEMM_ENOTUPLOADED;
@@ -403,6 +411,7 @@ int run(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K,
     c.cols_per_wave = o.cols_per_wave;
     c.k_slices = o.k_slices;
     c.slab_tiles = o.slab_tiles;
+    c.list_walk = o.list_walk;
     c.decode_wide_lists = o.decode_wide_lists != 0;
     c.event_before = static_cast<hipEvent_t>(o.event_before);
     c.event_after = static_cast<hipEvent_t>(o.event_after);
@@ -416,7 +425,7 @@ int run(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K,
         e = tst::launch_packed(X, t, b, Y, M, c);
     } else if (tst::decode_supported(M)) {
         e = tst::launch_decode(X, t, b, Y, M, c);
-    } else if (M <= 64) {
+    } else if (M <= 64 && tst::small_supported(l)) {
         if (!(l.forms & TCSC_FORM_CUTS)) return TSTGEMM_ENOFORM;
         e = tst::launch_small(X, t, b, Y, M, c);
     } else {

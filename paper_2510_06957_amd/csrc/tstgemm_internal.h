@@ -13,7 +13,7 @@ namespace tst {
 constexpr int kKBlock = 64;   // rows of W (entries of an X row) per K-block: one 64-bit row set per list piece
 constexpr int kColPad = 64;   // columns are padded to a multiple of this
 constexpr int kCutRows = 256; // rows of W per list cut of the small-tile kernel (its K-block)
-constexpr int kIndexSlack = 64;   // entries behind each index array that may be read (never used)
+constexpr int kIndexSlack = 256;  // entries behind each index array that may be read (never used)
 constexpr int kChunk5 = 16;       // groups of five rows (bytes) per column and chunk of the value-compression form
 // The workspace inside a handle's device buffer: room for 32 MiB of split-K partial sums and 128 MiB of the tiled,
 // transposed copy of X, or for one tile of 256 rows over the padded K if that is more.
@@ -89,6 +89,7 @@ struct Call {
     char *ws;            // scratch (256-byte aligned) or nullptr
     size_t ws_bytes;
     int cols_per_wave, k_slices, slab_tiles;   // 0 = built-in choice
+    int list_walk;       // small-tile kernel: 0 = built-in choice, 1 = plain, 2 = requests placed by hand
     bool decode_wide_lists;
     hipEvent_t event_before, event_after;      // both or neither
 
@@ -154,6 +155,7 @@ hipError_t launch_reduce(int C, const float *partials, const float *b, const Act
                          int m_tiles, int n_colgroups, int k_slices, int TM, hipStream_t stream);
 // tstgemm_small.hip -- lane-group gather-add kernel for 8 < M <= 64 (one tile of 64, 32 or 16 rows).
 hipError_t launch_small(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c);
+bool small_supported(const tcsc_layout_t &l);   // false: the lists are too long for its 32-bit offsets, use launch_large
 size_t small_tile_bytes(int M, int K);   // one tile of X for M <= 64 over the padded K
 // tstgemm_large.hip -- LDS-tiled gather-add kernel for M > 64.
 hipError_t launch_large(const float *X, const tcsc *t, const float *b, float *Y, int M, const Call &c);

@@ -13,8 +13,11 @@
 //   * the members come straight from the TCSC arrays (Sec. 2): the lists are ascending, so the piece of a list that
 //     falls into a block of rows of W (the paper's blocking, Sec. 3) is a slice of row_index_pos / _neg; the
 //     re-blocking pass stores where the slices start (list_cuts, a cut every 256 rows).  A lane loads 4 consecutive
-//     row numbers with one 16-byte load, 4 G per wavefront, one load ahead of their use; a row number costs one VALU
-//     instruction (shift and add to the lane's LDS address) and no scalar work;
+//     row numbers with one 16-byte load, 4 G per wavefront; a row number costs one VALU instruction (shift and add to
+//     the lane's LDS address) and no scalar work.  What the kernel waits for is these loads: a wavefront's loads
+//     return in order, and a step cannot start before its entries are there.  So the entries of a step are requested
+//     two steps ahead, the first entries of a slice a slice ahead and behind every other request of the slice
+//     before, and a step costs the vector ALU nothing but its four addresses and sixteen additions;
 //   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of the packed X tile in the LDS (64 KiB:
 //     256 rows of W at TM = 64, 512 at TM = 32, 1024 at TM = 16; tile[k][TM]) with a row of zeros in front of it for the slots behind
 //     the end of a slice; two workgroups share a compute unit, one computes while the other exchanges its tile;
@@ -44,7 +47,7 @@ template <int G> struct Geo {
     static constexpr int CUTS = ROWS / kCutRows;   // list cuts per block
     static constexpr int CH = 4 * G;            // list entries per wavefront and step
     static constexpr int PR = TM < 32 ? 32 : TM;   // rows of a partial tile (the reduction kernel works in units of 32 rows)
-    static_assert((1 << SH) == RB && CH <= kIndexSlack, "geometry");
+    static_assert((1 << SH) == RB && 2 * CH <= kIndexSlack, "geometry");
 };
 
 struct SmallArgs {
@@ -59,6 +62,167 @@ struct SmallArgs {
     int remap, alpha_stride;
 };
 
+// The lists are read through buffer loads: the address is a scalar descriptor (the array), a scalar byte offset (the
+// step; below 4 GiB, which small_supported() checks) and a lane offset, so a load costs no vector instruction.  The
+// loads are asm statements and so are the waits for them: a wavefront's loads return in order, the kernel keeps
+// several in flight at once (two steps of the slice in hand, the first steps of the next two slices), and which of
+// them a step needs follows from the order they were issued in, which the code below fixes -- the compiler, which
+// does not know how many of the conditional ones are in flight, can only wait for all of them.
+typedef int4v rsrc_t;
+__device__ __forceinline__ rsrc_t list_rsrc(const int32_t *list)
+{
+    // raw buffer, no stride, no range limit to speak of; 32-bit data (the word an untyped load ignores but must be valid)
+    const uintptr_t p = reinterpret_cast<uintptr_t>(list);
+    return rsrc_t{(int)(uint32_t)p, (int)(uint32_t)((p >> 32) & 0xffffu), 0x7fffffff, 0x00020000};
+}
+__device__ __forceinline__ void list_load(int4v &q, rsrc_t list, int lane_offset, int at)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=&v"(q) : "v"(lane_offset), "s"(list), "s"(at) : "memory");
+}
+// At most LEFT loads outstanding: all but the youngest LEFT have arrived.  The wait takes the value it makes valid as
+// a read-write operand, so that whatever uses or copies it is data-dependent on the wait.
+template <int LEFT> __device__ __forceinline__ void loaded(int4v &q)
+{
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(q) : "n"(LEFT));
+}
+// A slice of n entries is walked as  n % CH  entries first (the partly filled step, if any) and whole steps of CH
+// entries behind it.  A whole step: lane group g takes entries 4 g .. 4 g + 3, one 16-byte load per lane.  The partly
+// filled step takes s = ceil(entries / G) gathers instead of four (two or four are issued): lane group g takes entries
+// s g .. s g + s - 1, so a lane still loads its entries with one 16-byte load (what lies behind its s entries, or
+// behind the end of the slice, is loaded and not used; the index arrays have that much slack).
+// This lane's entries of the first step of a slice of n entries that starts at entry `first` of the list.
+template <int G> __device__ __forceinline__ void load_head(int4v &q, rsrc_t list, int first, int n, int g)
+{
+    const int head = n & (Geo<G>::CH - 1);
+    const int slots = head ? (head + G - 1) / G : 4;
+    list_load(q, list, __mul24(g, 4 * slots), 4 * first);
+}
+
+// LDS reads as asm statements: nothing is scheduled between the instructions of one statement, and the waits are
+// placed by hand.  The reads return in order, so "at most LEFT outstanding" means that all but the youngest LEFT have
+// arrived.  A wait takes the values it makes valid as read-write operands: whatever uses or copies them is
+// data-dependent on the wait and cannot be placed in front of it.  (A scalar load in flight at the same time only
+// makes a wait longer.)  Every read is waited for before the slice ends.
+template <int LEFT> __device__ __forceinline__ void arrived(float4v &x, float4v &y)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(LEFT));
+}
+template <int LEFT> __device__ __forceinline__ void arrived(float4v &x, float4v &y, float4v &sums)
+{
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(x), "+v"(y), "+v"(sums) : "n"(LEFT));   // ... and behind what was added before
+}
+// The four gathers of a whole step: address = (row number << SH) + base (one VALU instruction; base is the lane's
+// LDS address of row 0 of the W block minus the block's first row times the row size), then the 16-byte read; the
+// address register is reused (an LDS instruction takes its address when it is issued).  While it queues its reads
+// the wavefront runs at a raised priority (about 1 % faster).  The statement starts with the wait for the entries
+// (at most LEFT younger loads still in flight), so the registers it reads are the ones the load wrote.
+#define TST_STEP(wait) \
+    asm volatile(wait "s_setprio 1\n\t" \
+                 "v_lshl_add_u32 %[a], %[q0], %[sh], %[base]\n\tds_read_b128 %[v0], %[a]\n\t" \
+                 "v_lshl_add_u32 %[a], %[q1], %[sh], %[base]\n\tds_read_b128 %[v1], %[a]\n\t" \
+                 "v_lshl_add_u32 %[a], %[q2], %[sh], %[base]\n\tds_read_b128 %[v2], %[a]\n\t" \
+                 "v_lshl_add_u32 %[a], %[q3], %[sh], %[base]\n\tds_read_b128 %[v3], %[a]\n\t" \
+                 "s_setprio 0" \
+                 : [a] "=&v"(a), [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), [v3] "=&v"(v[3]) \
+                 : [q0] "v"(q[0]), [q1] "v"(q[1]), [q2] "v"(q[2]), [q3] "v"(q[3]), [sh] "n"(SH), [base] "v"(base) \
+                 : "memory")
+template <int SH, int LEFT> __device__ __forceinline__ void read_step(float4v (&v)[4], const int4v &q, int base)
+{
+    int a;
+    static_assert(LEFT >= -1 && LEFT <= 2, "waits");
+    if constexpr (LEFT == 2) TST_STEP("s_waitcnt vmcnt(2)\n\t");
+    else if constexpr (LEFT == 1) TST_STEP("s_waitcnt vmcnt(1)\n\t");
+    else if constexpr (LEFT == 0) TST_STEP("s_waitcnt vmcnt(0)\n\t");
+    else TST_STEP("");   // the entries are there already
+}
+#undef TST_STEP
+// Two or four gathers at ready-made addresses (the partly filled step).
+__device__ __forceinline__ void read_two(float4v (&v)[4], int a0, int a1)
+{
+    asm volatile("s_setprio 1\n\tds_read_b128 %[v0], %[a0]\n\tds_read_b128 %[v1], %[a1]\n\ts_setprio 0"
+                 : [v0] "=&v"(v[0]), [v1] "=&v"(v[1]) : [a0] "v"(a0), [a1] "v"(a1) : "memory");
+}
+__device__ __forceinline__ void read_four(float4v (&v)[4], int a0, int a1, int a2, int a3)
+{
+    asm volatile("s_setprio 1\n\tds_read_b128 %[v0], %[a0]\n\tds_read_b128 %[v1], %[a1]\n\t"
+                 "ds_read_b128 %[v2], %[a2]\n\tds_read_b128 %[v3], %[a3]\n\ts_setprio 0"
+                 : [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), [v3] "=&v"(v[3])
+                 : [a0] "v"(a0), [a1] "v"(a1), [a2] "v"(a2), [a3] "v"(a3) : "memory");
+}
+
+// A slice of n entries of a list r, from entry `first` on; h holds this lane's entries of its first step, requested
+// two slices ago and arrived.  Once they have become LDS addresses, `next` requests into the same registers what
+// the slice after the next one starts with (load_head).  Order of the requests: the whole steps of this slice one
+// after the other, each two steps ahead of its use, and `next` right behind the last of them -- so a step never
+// waits for more than its own entries and what was requested before them, and at the start of every slice exactly
+// two requests are in flight, its own and the next slice's.  zero_row is the lane's address in the row of zeros in
+// front of the block: in a slot of the partly filled step where its lane group has no entry a lane gathers that.
+template <int G, bool NEG, typename Next>
+__device__ __forceinline__ void run_slice(float4v &acc, const int4v &h, rsrc_t r, int first, int n, int base,
+                                          int zero_row, int g, Next next)
+{
+    constexpr int CH = Geo<G>::CH, SH = Geo<G>::SH;
+    const int head = n & (CH - 1);
+    int at = 4 * (first + head);   // byte offset of the first whole step
+    int left = (n - head) / CH;    // whole steps to go
+    int4v qa, qb;                  // the entries of the two steps behind the one in hand
+    asm volatile("" : "=v"(qa), "=v"(qb));   // (defined as far as the compiler is concerned: no code to initialise them)
+    float4v v[4];
+    auto sums2 = [&]() {
+        arrived<0>(v[0], v[1]);
+        if constexpr (NEG) { acc -= v[0]; acc -= v[1]; } else { acc += v[0]; acc += v[1]; }
+    };
+    auto sums4 = [&]() {
+        arrived<2>(v[0], v[1]);
+        if constexpr (NEG) { acc -= v[0]; acc -= v[1]; } else { acc += v[0]; acc += v[1]; }
+        arrived<0>(v[2], v[3], acc);
+        if constexpr (NEG) { acc -= v[2]; acc -= v[3]; } else { acc += v[2]; acc += v[3]; }
+    };
+    const int lane16 = 16 * g;
+    const int slots = (head + G - 1) / G;   // wave-uniform: gathers of the partly filled step, 0 if there is none
+    if (head) {
+        const int mine = min(head - __mul24(g, slots), slots);   // this lane group has entries in slots 0 .. mine - 1
+        const int a0 = mine > 0 ? (h[0] << SH) + base : zero_row;
+        const int a1 = mine > 1 ? (h[1] << SH) + base : zero_row;
+        // two independent tests, not an else: the sums stay where they are on both paths
+        if (slots <= 2) read_two(v, a0, a1);
+        if (slots > 2) {
+            const int a2 = mine > 2 ? (h[2] << SH) + base : zero_row;
+            const int a3 = mine > 3 ? (h[3] << SH) + base : zero_row;
+            read_four(v, a0, a1, a2, a3);
+        }
+    }
+    // (a slice without a partly filled step, one in CH, has the entries of its first whole step in h; they are
+    // requested once more, which keeps the steps below the same for every slice)
+    if (left > 0) list_load(qa, r, lane16, at);
+    if (left > 1) list_load(qb, r, lane16, at + 4 * CH);
+    if (left <= 2) next();
+    if (head) {
+        if (slots <= 2) sums2();
+        if (slots > 2) sums4();
+    }
+    // Whole steps, two per turn.  In flight when a step is about to start: its own entries, those of the step behind
+    // it if there is one, and `next` once the last step's entries have been requested: two younger requests when two
+    // steps are left, one otherwise.
+    while (left > 0) {
+        if (left == 2) read_step<SH, 2>(v, qa, base); else read_step<SH, 1>(v, qa, base);
+        if (left > 2) {
+            list_load(qa, r, lane16, at + 8 * CH);
+            if (left == 3) next();
+        }
+        sums4();
+        if (--left == 0) break;
+        if (left == 2) read_step<SH, 2>(v, qb, base); else read_step<SH, 1>(v, qb, base);
+        if (left > 2) {
+            list_load(qb, r, lane16, at + 12 * CH);
+            if (left == 3) next();
+        }
+        sums4();
+        --left;
+        at += 8 * CH;
+    }
+}
+
 // Four gathers of the wavefront: tile rows k[0..3] (per lane group), this lane's four X rows of each.  base is the
 // lane's LDS address of row 0 of the W block minus the block's first row times the row size, so that
 // address = (row number << SH) + base needs no subtraction.
@@ -68,12 +232,15 @@ template <int SH> __device__ __forceinline__ void gather4(float4v (&v)[4], const
     for (int t = 0; t < 4; ++t) v[t] = *reinterpret_cast<lds_f4_ptr>((k[t] << SH) + base);
 }
 
+// The walk for short slices (low density), where a wavefront's time is the number of instructions it gets through,
+// scalar ones and branches included, and the bookkeeping of the walk above costs more than it saves: every step is four
+// gathers, whole or not, and the loads are left to the compiler.
 // A slice of n entries of a list: lane group g takes entries CH c + 4 g .. + 3 of step c; p points at the lane's
 // entries of step 0 and q holds them (loaded by the caller, one slice ahead).  Entries behind the end of the slice
 // (up to CH - 1 are loaded beyond it; the index arrays have that much slack) are replaced by k_zero, the row in
 // front of the block, which holds zeros.
 template <int G, bool NEG>
-__device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *__restrict__ p, int n, int base,
+__device__ __forceinline__ void run_short_slice(float4v &acc, int4v q, const int32_t *__restrict__ p, int n, int base,
                                           int k_zero, int g)
 {
     constexpr int CH = Geo<G>::CH, SH = Geo<G>::SH;
@@ -97,7 +264,8 @@ __device__ __forceinline__ void run_slice(float4v &acc, int4v q, const int32_t *
     }
 }
 
-template <int NCW, int G>
+// LONG: the walk with hand-placed requests and waits (run_slice), for slices of a few steps; else the plain one.
+template <int NCW, int G, bool LONG>
 __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
 {
     using geo = Geo<G>;
@@ -150,38 +318,81 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
         __syncthreads();
         const int lds0 = (int)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         const int lane_base = lds0 + RB + r * 16;     // this lane's part of tile row 0
-        // first step of a slice: this lane's 4 entries, loaded one slice ahead of their use
-        auto first_step = [&](const int32_t *rows, int at) {
-            return int4v(*reinterpret_cast<const int4v_unaligned *>(rows + at + 4 * g));
-        };
-        int4v q = first_step(a.rip, lo[0]);
-        for (int c = blk0; c < blk1; ++c) {
-            load_cut(hi, c + 1);
-            const int base = lane_base - c * STAGE;   // tile row 0 is row c * ROWS of W
-            const int k_zero = c * geo::ROWS - 1;
-#pragma unroll
-            for (int j = 0; j < NCW; ++j) {
-                int4v qn = first_step(a.rin, lo[2 * j + 1]);
-                // The column's sums are a value of their own while its lists are walked and the array is only touched
-                // here: updated in place inside the loops, the whole array went through copies (and, with four
-                // columns, spills) at every step.
-                float4v sum = acc[j];
-                run_slice<G, false>(sum, q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
-                // behind the last column: the first slice of the next block starts where this block's ended
-                q = first_step(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
-                run_slice<G, true>(sum, qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
-                acc[j] = sum;
-            }
-#pragma unroll
-            for (int i = 0; i < 2 * NCW; ++i) lo[i] = hi[i];
-            if (c + 1 == blk1) break;
-            // exchange the tile (as in the large-M kernel: requests before the barrier, copies behind it)
-            stage_load(c + 1);
+        // exchange the tile (as in the large-M kernel: requests before the barrier, copies behind it)
+        auto exchange = [&](int c) {
+            stage_load(c);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             stage_store();
             __syncthreads();
+        };
+        if constexpr (LONG) {
+            int nx[2 * NCW];
+            load_cut(hi, blk0 + 1);
+            // h0: the first entries of the +1 slice about to be walked (or, while a -1 slice is walked, of the next +1
+            // slice), h1: the same for the -1 slices.  A slice requests those of the slice after the next one.
+            const rsrc_t rp = list_rsrc(a.rip), rn = list_rsrc(a.rin);
+            int4v h0, h1;
+            load_head<G>(h0, rp, lo[0], hi[0] - lo[0], g);
+            load_head<G>(h1, rn, lo[1], hi[1] - lo[1], g);
+            for (int c = blk0; c < blk1; ++c) {
+                load_cut(nx, c + 2);   // the borders of the next block's slices, for the requests at the end of this block
+                const int base = lane_base - c * STAGE;   // tile row 0 is row c * ROWS of W
+#pragma unroll
+                for (int j = 0; j < NCW; ++j) {
+                    // The column's sums are a value of their own while its lists are walked and the array is only touched
+                    // here: updated in place inside the loops, the whole array went through copies (and, with four
+                    // columns, spills) at every step.
+                    float4v sum = acc[j];
+                    // the next column's lists, or the first column's in the next block
+                    const int p_first = j + 1 < NCW ? lo[2 * j + 2] : hi[0], p_n = (j + 1 < NCW ? hi[2 * j + 2] : nx[0]) - p_first;
+                    const int n_first = j + 1 < NCW ? lo[2 * j + 3] : hi[1], n_n = (j + 1 < NCW ? hi[2 * j + 3] : nx[1]) - n_first;
+                    loaded<1>(h0);
+                    run_slice<G, false>(sum, h0, rp, lo[2 * j], hi[2 * j] - lo[2 * j], base, lane_base - RB, g,
+                                        [&]() { load_head<G>(h0, rp, p_first, p_n, g); });
+                    loaded<1>(h1);
+                    run_slice<G, true>(sum, h1, rn, lo[2 * j + 1], hi[2 * j + 1] - lo[2 * j + 1], base, lane_base - RB, g,
+                                       [&]() { load_head<G>(h1, rn, n_first, n_n, g); });
+                    acc[j] = sum;
+                }
+#pragma unroll
+                for (int i = 0; i < 2 * NCW; ++i) { lo[i] = hi[i]; hi[i] = nx[i]; }
+                if (c + 1 == blk1) break;
+                exchange(c + 1);
+            }
+            // the last two slices' requests (for slices that do not exist) are still in flight: they must have landed
+            // before their registers are used for anything else
+            loaded<0>(h0);
+            loaded<0>(h1);
+        } else {
+            // first step of a slice: this lane's 4 entries, loaded one slice ahead of their use
+            auto first_step = [&](const int32_t *rows, int at) {
+                return int4v(*reinterpret_cast<const int4v_unaligned *>(rows + at + 4 * g));
+            };
+            int4v q = first_step(a.rip, lo[0]);
+            for (int c = blk0; c < blk1; ++c) {
+                load_cut(hi, c + 1);
+                const int base = lane_base - c * STAGE;   // tile row 0 is row c * ROWS of W
+                const int k_zero = c * geo::ROWS - 1;
+#pragma unroll
+                for (int j = 0; j < NCW; ++j) {
+                    int4v qn = first_step(a.rin, lo[2 * j + 1]);
+                    // The column's sums are a value of their own while its lists are walked and the array is only touched
+                    // here: updated in place inside the loops, the whole array went through copies (and, with four
+                    // columns, spills) at every step.
+                    float4v sum = acc[j];
+                    run_short_slice<G, false>(sum, q, a.rip + lo[2 * j] + 4 * g, hi[2 * j] - lo[2 * j], base, k_zero, g);
+                    // behind the last column: the first slice of the next block starts where this block's ended
+                    q = first_step(a.rip, j + 1 < NCW ? lo[2 * j + 2] : hi[0]);
+                    run_short_slice<G, true>(sum, qn, a.rin + lo[2 * j + 1] + 4 * g, hi[2 * j + 1] - lo[2 * j + 1], base, k_zero, g);
+                    acc[j] = sum;
+                }
+#pragma unroll
+                for (int i = 0; i < 2 * NCW; ++i) lo[i] = hi[i];
+                if (c + 1 == blk1) break;
+                exchange(c + 1);
+            }
         }
     }
 
@@ -222,7 +433,7 @@ __global__ void __launch_bounds__(NT, 8) k_small(const SmallArgs a)
     }
 }
 
-template <int NCW, int G>
+template <int NCW, int G, bool LONG>
 hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M, int k_slices, const Call &c)
 {
     using geo = Geo<G>;
@@ -256,7 +467,7 @@ hipError_t launch(const float *X, const tcsc *t, const float *b, float *Y, int M
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     a.remap = (grid % 8 == 0) ? (int)(grid / 8) : 0;
     if ((e = c.record_before()) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_small<NCW, G>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL((k_small<NCW, G, LONG>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     e = hipGetLastError();
     if (e == hipSuccess) e = c.record_after();
     if (e != hipSuccess || k_slices == 1) return e;
@@ -274,6 +485,7 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, float *Y,
 {
     if (M > 64) return hipErrorInvalidValue;
     const tcsc_layout_t &l = t->layout;
+    if (!small_supported(l)) return hipErrorInvalidValue;
     const bool short_k = l.n_cuts <= 4;
     const int G = M <= 16 ? 16 : M <= 32 ? 8 : 4;
     const int slots = 2 * compute_units();
@@ -288,17 +500,38 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, float *Y,
     const long long groups = l.n_pad / (NW * ncw);
     int k_slices = c.k_slices;
     if (k_slices == 0) k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
-    switch (G * 8 + ncw) {
-    case 16 * 8 + 1: return launch<1, 16>(X, t, b, Y, M, k_slices, c);
-    case 16 * 8 + 2: return launch<2, 16>(X, t, b, Y, M, k_slices, c);
-    case 16 * 8 + 4: return launch<4, 16>(X, t, b, Y, M, k_slices, c);
-    case 8 * 8 + 1: return launch<1, 8>(X, t, b, Y, M, k_slices, c);
-    case 8 * 8 + 2: return launch<2, 8>(X, t, b, Y, M, k_slices, c);
-    case 8 * 8 + 4: return launch<4, 8>(X, t, b, Y, M, k_slices, c);
-    case 4 * 8 + 1: return launch<1, 4>(X, t, b, Y, M, k_slices, c);
-    case 4 * 8 + 2: return launch<2, 4>(X, t, b, Y, M, k_slices, c);
-    default: return launch<4, 4>(X, t, b, Y, M, k_slices, c);
+    // Which walk of the lists: by the mean length of a slice (the entries of one list inside one block of rows of W) in
+    // steps of the wavefront (4 G entries).  Measured, time of the kernel with the requests placed by hand against the
+    // plain walk: 4 steps (M = 64 and M = 16 at 50 %) 6 % and 9 % faster; 2 steps (M = 64 and M = 32 at 25 %) 5 % and
+    // 1.5 % slower; 1 step and less (M = 64 at 12.5 % and 6.25 %) 19 % and 13 % slower.  From 3 steps on it is taken.
+    const int block_rows = STAGE / (4 * (256 / G));
+    const long long n_blocks = (l.K + block_rows - 1) / block_rows;
+    const bool long_slices = c.list_walk ? c.list_walk == 2
+                                         : (double)(l.nnz_pos + l.nnz_neg) >= 2.0 * (3.0 * 4 * G) * (double)n_blocks * (double)l.N;
+    const int shape = G * 8 + ncw;
+#define TST_SMALL(NCW_, G_) \
+    case G_ * 8 + NCW_: \
+        return long_slices ? launch<NCW_, G_, true>(X, t, b, Y, M, k_slices, c) : launch<NCW_, G_, false>(X, t, b, Y, M, k_slices, c)
+    switch (shape) {
+        TST_SMALL(1, 16);
+        TST_SMALL(2, 16);
+        TST_SMALL(4, 16);
+        TST_SMALL(1, 8);
+        TST_SMALL(2, 8);
+        TST_SMALL(4, 8);
+        TST_SMALL(1, 4);
+        TST_SMALL(2, 4);
+    default:
+        return long_slices ? launch<4, 4, true>(X, t, b, Y, M, k_slices, c) : launch<4, 4, false>(X, t, b, Y, M, k_slices, c);
     }
+#undef TST_SMALL
+}
+
+// The small-tile kernel addresses a list with 32-bit byte offsets: lists of 2^30 entries or more are not for it (the
+// large-M kernel takes any number of rows of X).
+bool small_supported(const tcsc_layout_t &l)
+{
+    return l.nnz_pos + kIndexSlack < (1LL << 30) && l.nnz_neg + kIndexSlack < (1LL << 30);
 }
 
 // Bytes of the one tile of X (M <= 64 rows: 64, 32 or 16 rows per tile) over K padded to whole blocks.

@@ -207,20 +207,42 @@ def test_low_density_tall_and_wide_picks_its_own_shape():
 @pytest.mark.parametrize("M,K,N,density", [(64, 1100, 200, 0.5), (33, 257, 70, 0.5), (9, 2100, 40, 0.0625),
                                            (50, 600, 130, 1.0), (16, 256, 64, 0.25), (32, 1100, 100, 0.5),
                                            (20, 513, 40, 0.25), (31, 1536, 64, 1.0)])
-def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density):
+@pytest.mark.parametrize("list_walk", [1, 2])
+def test_small_tile_launch_shapes(cols_per_wave, k_slices, M, K, N, density, list_walk):
     """The path for 8 < M <= 64 (one tile of 64 rows with blocks of 256 rows of W, or of 32 rows with blocks of 512):
     lists shorter and longer than one step of the wavefront, empty slices, K below, at and above the block size, a
-    last block that ends early, with and without K slices."""
+    last block that ends early, with and without K slices; both walks of the lists on every case."""
     W, X, b = si.make_inputs(M, K, N, density, "normal", seed=61 + M)
     _, Xi, _ = si.make_inputs(M, K, N, density, "int8", seed=62 + M)
     ot = oracle.tcsc_build(W)
     Yd, A, _ = oracle.tstgemm(X, ot, b)
     Ydi, _, _ = oracle.tstgemm(Xi, ot, b)
-    shape = dict(cols_per_wave=cols_per_wave, k_slices=k_slices)
+    shape = dict(cols_per_wave=cols_per_wave, k_slices=k_slices, list_walk=list_walk)
     Y, h = gpu_tstgemm(W, X, b, **shape)
-    assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices}")
+    assert_close(Y, Yd, A, f"ncw={cols_per_wave} ks={k_slices} walk={list_walk}")
     Yi, _ = gpu_tstgemm(W, Xi, b, handle=h, **shape)
     assert np.array_equal(Yi, Ydi.astype(np.float32))
+
+
+@pytest.mark.parametrize("list_walk", [1, 2])
+@pytest.mark.parametrize("M,K,N,density", [(64, 700, 48, d) for d in (0.02, 0.1, 0.3, 0.7, 1.0)] +
+                                          [(16, 2500, 48, d) for d in (0.02, 0.3, 1.0)] + [(32, 1300, 32, 0.6)])
+def test_small_tile_slice_lengths(M, K, N, density, list_walk):
+    """Slices of every length -- none, a few entries, a partly filled step alone, one to sixteen whole steps with and
+    without a partly filled one in front (a column of a block of 256 / 1024 rows holds 0 .. 256 / 1024 entries of one
+    sign; the random matrices make all of these lengths over their columns and blocks) -- through both walks."""
+    W, X, b = si.make_inputs(M, K, N, density, "normal", seed=81 + M)
+    # a few columns of one sign only and one empty column: the longest and the shortest slices there are
+    W[:, 0] = 1
+    W[:, 1] = -1
+    W[:, 2] = 0
+    _, Xi, _ = si.make_inputs(M, K, N, density, "int8", seed=82 + M)
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b, list_walk=list_walk)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N} d={density} walk={list_walk}")
+    Yi, _ = gpu_tstgemm(W, Xi, b, handle=h, list_walk=list_walk)
+    assert np.array_equal(Yi, oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
 
 
 @pytest.mark.parametrize("M,K,N,density", [(40, 40000, 70, 0.25), (64, 300, 20000, 0.5), (20, 70000, 33, 0.0625),

@@ -162,6 +162,7 @@ def test_options_reject_bad_values():
     assert call(struct_size=8) == -1
     assert call(cols_per_wave=3) == -1 and call(k_slices=9) == -1 and call(k_slices=-1) == -1 and call(slab_tiles=-1) == -1
     assert call(cols_per_wave=4, k_slices=8, slab_tiles=2) == -3
+    assert call(list_walk=3) == -1 and call(list_walk=-1) == -1 and call(list_walk=2) == -3
     assert call(event_before=1) == -1 and call(event_after=1) == -1 and call(event_before=1, event_after=2) == -3
     assert call(encoding=3) == -1 and call(encoding=-1) == -1
     assert call(encoding=1) == -1 and call(M=8, encoding=1) == -3 and call(M=8, encoding=2) == -3   # M <= 8 only
