@@ -32,6 +32,8 @@ constexpr int kDecodeWaves = kDecodeThreads / 64;
 constexpr int kDecodeMaxLds = 150 * 1024;
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 
 // Butterfly sum over the 64 lanes of each of the MM values; every lane ends with all totals.
 template <int MM> __device__ __forceinline__ void wave_sum(float (&v)[MM])
@@ -166,11 +168,65 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
     const int n_chunks = CHUNKED ? (K + kc - 1) / kc : 1;
     const int n_batches = (N + waves_total - 1) / waves_total;
 
+    // Row k of the chunk in the LDS: one write per plane (16 bytes for a full plane: a plane's row k is 16-byte
+    // aligned), not one per row of X -- with single floats 16 bytes apart four lanes share a bank.
+    auto store_row = [&](int k, const float (&x)[MM]) {
+#pragma unroll
+        for (int p0 = 0; p0 < MM; p0 += 4) {
+            constexpr int kFull = 4;
+            const int width = MM - p0 < kFull ? MM - p0 : kFull;
+            float *dst = xs + xs_at<MM>(k, p0, kc1);
+            if (width == 4) *reinterpret_cast<float4v *>(dst) = float4v{x[p0], x[p0 + 1 < MM ? p0 + 1 : p0], x[p0 + 2 < MM ? p0 + 2 : p0], x[p0 + 3 < MM ? p0 + 3 : p0]};
+            else if (width == 3) { dst[0] = x[p0]; dst[1] = x[p0 + 1 < MM ? p0 + 1 : p0]; dst[2] = x[p0 + 2 < MM ? p0 + 2 : p0]; }   // rows of 12 bytes: no alignment to speak of
+            else if (width == 2) *reinterpret_cast<float2v *>(dst) = float2v{x[p0], x[p0 + 1 < MM ? p0 + 1 : p0]};
+            else dst[0] = x[p0];
+        }
+    };
+    // The chunk of X a workgroup works on, transposed into the LDS.  For one or two rows of X, where the call is short
+    // and this is a visible part of it, all requests of a thread go out before its first write (with a write behind
+    // each request a thread waited for memory once per 1024 rows of the chunk: four times for K = 4096, about 1 us of
+    // a 14 us call), and where the rows of X are 16-byte aligned a thread takes four consecutive k with one 16-byte
+    // load.  With more rows of X neither changed the time of a call (M = 4, M = 8), so they keep the plain loop.
     auto load_chunk = [&](int c) {
         const int k_lo = c * kc, len = min(kc, K - k_lo);
-        for (int k = threadIdx.x; k < len; k += kDecodeThreads) {
+        const float *Xc = X + k_lo;
+        if constexpr (MM <= 2 && !CHUNKED) {
+            const bool aligned = (((unsigned)K | (unsigned)len) & 3u) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+            if (aligned) {
+                for (int k4 = 4 * threadIdx.x; k4 < len; k4 += 4 * kDecodeThreads) {
+                    float4v x4[MM];
 #pragma unroll
-            for (int m = 0; m < MM; ++m) xs[xs_at<MM>(k, m, kc1)] = X[(size_t)m * K + k_lo + k];
+                    for (int m = 0; m < MM; ++m) x4[m] = *reinterpret_cast<const float4v *>(Xc + (size_t)m * K + k4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float x[MM];
+#pragma unroll
+                        for (int m = 0; m < MM; ++m) x[m] = x4[m][i];
+                        store_row(k4 + i, x);
+                    }
+                }
+            } else {
+                for (int k0 = threadIdx.x; k0 < len; k0 += 4 * kDecodeThreads) {
+                    float x[4][MM];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int m = 0; m < MM; ++m) {
+                            const int k = k0 + i * kDecodeThreads;
+                            x[i][m] = k < len ? Xc[(size_t)m * K + k] : 0.f;
+                        }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (k0 + i * kDecodeThreads < len) store_row(k0 + i * kDecodeThreads, x[i]);
+                }
+            }
+        } else {
+            for (int k = threadIdx.x; k < len; k += kDecodeThreads) {
+                float x[MM];
+#pragma unroll
+                for (int m = 0; m < MM; ++m) x[m] = Xc[(size_t)m * K + k];
+                store_row(k, x);
+            }
         }
     };
     if (threadIdx.x < MM) xs[xs_at<MM>(kc, threadIdx.x, kc1)] = 0.f;
