@@ -29,7 +29,8 @@ namespace {
 
 constexpr int kDecodeThreads = 1024;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
-constexpr int kDecodeMaxLds = 150 * 1024;
+constexpr int kDecodeMaxLds = 150 * 1024;   // ... for X
+constexpr int kSlotColumns = 64;            // columns whose two list sums a workgroup keeps in the LDS at a time
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -155,7 +156,7 @@ template <int MM, bool CHUNKED, int FORM>
 __global__ void __launch_bounds__(kDecodeThreads)
 k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int32_t *__restrict__ csn,
          const void *__restrict__ rip_, const void *__restrict__ rin_, const float *__restrict__ b,
-         const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N, int kc)
+         const float *__restrict__ alpha, int alpha_stride, float *__restrict__ Y, int K, int N, int kc, int deal_lists)
 {
     static_assert(!(FORM == 2 && CHUNKED), "the padded 16-bit lists need all of X in the LDS");
     constexpr bool SIGNED = FORM == 1;
@@ -233,6 +234,42 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
     if (!CHUNKED) load_chunk(0);   // all of X fits: loaded once, for all columns of this workgroup
     __syncthreads();
 
+    if (FORM == 2 && deal_lists) {
+        // Lists, not columns, are dealt to the wavefronts: a workgroup takes a run of columns, wavefront w the lists
+        // w, w + 16, ... of the run (list 2 c: the +1 list of its column c, 2 c + 1: the -1 list), and the two sums of
+        // a column meet in the LDS.  The launch takes this when whole columns per wavefront would leave much of the
+        // chip idle (N = 11008: 2.7 columns per wavefront of a chip-filling grid, so a third of the grid is left out and
+        // 88 compute units do twice the work of the others) and the second sum over the wavefront per column is cheap
+        // (one or two rows of X).
+        float *const slot = xs + (size_t)MM * kc1;   // [kSlotColumns][2][MM] behind the planes of X
+        const int per_wg = (N + (int)gridDim.x - 1) / (int)gridDim.x;
+        const int c_begin = min(N, (int)blockIdx.x * per_wg), c_end = min(N, c_begin + per_wg);
+        for (int c0 = c_begin; c0 < c_end; c0 += kSlotColumns) {
+            const int columns = min(kSlotColumns, c_end - c0);
+            for (int u = wave; u < 2 * columns; u += kDecodeWaves) {
+                const int n = c0 + (u >> 1);
+                float acc[MM];
+#pragma unroll
+                for (int m = 0; m < MM; ++m) acc[m] = 0.f;
+                if (u & 1) run_list16<MM, true>(acc, static_cast<const uint16_t *>(rin_), csn[n], csn[n + 1], xs, kc1, lane);
+                else run_list16<MM, false>(acc, static_cast<const uint16_t *>(rip_), csp[n], csp[n + 1], xs, kc1, lane);
+                wave_sum<MM>(acc);
+#pragma unroll
+                for (int m = 0; m < MM; ++m)
+                    if (lane == m) slot[u * MM + m] = acc[m];
+            }
+            __syncthreads();
+            // Y = (sum of the +1 list) + (minus the sum of the -1 list) + b, bias last; consecutive threads take
+            // consecutive columns
+            for (int i = threadIdx.x; i < columns * MM; i += kDecodeThreads) {
+                const int m = i / columns, c = i - m * columns, n = c0 + c;
+                const float sum = slot[2 * c * MM + m] + slot[(2 * c + 1) * MM + m];
+                Y[(size_t)m * N + n] = activate(sum + (b ? b[n] : 0.f), alpha, alpha_stride, n);
+            }
+            if (c0 + kSlotColumns < c_end) __syncthreads();   // the slots are written again
+        }
+        return;
+    }
     // Every wavefront of the workgroup goes through the same number of batches and chunks (the barriers inside);
     // a wavefront without a column in the last batch just has empty lists.
     for (int batch = 0; batch < n_batches; ++batch) {
@@ -273,7 +310,7 @@ k_decode(const float *__restrict__ X, const int32_t *__restrict__ csp, const int
 }
 
 template <int MM, bool CHUNKED, int FORM>
-hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, float *Y, int kc, size_t lds, const Call &c)
+hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, float *Y, int kc, size_t lds, const Call &c)   // lds: bytes for X
 {
     const DeviceTcsc d = device_view(t);
     const hipStream_t stream = c.stream;
@@ -286,18 +323,34 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, float *Y
     const unsigned long long bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0;
     if ((attr_devices.load(std::memory_order_relaxed) & bit) == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode<MM, CHUNKED, FORM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kDecodeMaxLds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kDecodeMaxLds + kSlotColumns * 2 * MM * (int)sizeof(float));
         if (e != hipSuccess) return e;
         attr_devices.fetch_or(bit, std::memory_order_relaxed);
     }
-    const int per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
-    int grid = compute_units() * per_cu;
+    // Whole columns per wavefront, every wavefront the same number, one after the other (with 1.3 columns per
+    // wavefront a full grid would leave two thirds of the wavefronts, and of the loads in flight, idle during the
+    // second round), or -- 16-bit lists, one or two rows of X -- the lists of a run of columns dealt to the wavefronts
+    // of a workgroup, which fills every compute unit alike at the price of a second sum over the wavefront per column
+    // (measured, M = 1: N = 11008 13.0 -> 12.5 us, N = 16384, where whole columns fit exactly, 15.9 -> 16.7 us; M = 8:
+    // 24.5 -> 28.0 us).  The second is taken when the first would use less than 85 % of the slots of its rounds.
+    const size_t lds_dealt = lds + (size_t)kSlotColumns * 2 * MM * sizeof(float);
     const int need = (t->N + kDecodeWaves - 1) / kDecodeWaves;
+    int per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
+    int grid = compute_units() * per_cu;
     if (grid > need) grid = need;
-    // every wavefront takes the same number of columns, one after the other: with 1.3 columns per wavefront a full grid
-    // would leave two thirds of the wavefronts (and of the loads in flight) idle during the second round
     const int rounds = (need + grid - 1) / grid;
-    grid = (need + rounds - 1) / rounds;
+    int deal_lists = 0;
+    if (FORM == 2 && MM <= 2 && (double)need < 0.85 * (double)rounds * (double)grid) {
+        deal_lists = 1;
+        lds = lds_dealt;
+        per_cu = lds * 2 <= (size_t)160 * 1024 ? 2 : 1;
+        grid = compute_units() * per_cu;
+        const int lists_need = (t->N + kDecodeWaves / 2 - 1) / (kDecodeWaves / 2);   // at least one list per wavefront
+        if (grid > lists_need) grid = lists_need;
+    } else {
+        grid = (need + rounds - 1) / rounds;
+    }
     hipError_t e;
     if ((e = c.record_before()) != hipSuccess) return e;
     const int32_t *cs_pos = FORM == 2 ? d.col_start16_pos : d.col_start_pos;
@@ -307,7 +360,7 @@ hipError_t launch_kernel(const float *X, const tcsc *t, const float *b, float *Y
                                         : static_cast<const void *>(d.row_index_pos);
     const void *lists_neg = FORM == 2 ? static_cast<const void *>(d.row_index16_neg) : static_cast<const void *>(d.row_index_neg);
     hipLaunchKernelGGL((k_decode<MM, CHUNKED, FORM>), dim3(grid), dim3(kDecodeThreads), lds, stream, X, cs_pos, cs_neg,
-                       lists_pos, lists_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N, kc);
+                       lists_pos, lists_neg, b, act.alpha, act.alpha_stride, Y, t->K, t->N, kc, deal_lists);
     e = hipGetLastError();
     if (e == hipSuccess) e = c.record_after();
     return e;

@@ -571,3 +571,25 @@ def test_decode_list_widths(M, K, N):
     Ywi, _ = gpu_tstgemm(W, Xi, b, handle=h, wide_lists=True)
     assert_close(Yw, Yd, A, f"{M}x{K}x{N}, 32-bit lists")
     assert np.array_equal(Ywi, Ydi)
+
+
+@pytest.mark.parametrize("M", [1, 2])
+@pytest.mark.parametrize("K,N", [(300, 9000), (300, 8192), (257, 33000), (4096, 70), (64, 11008)])
+def test_decode_whole_columns_and_dealt_lists(M, K, N):
+    """One or two rows of X on the 16-bit lists: the launch either gives every wavefront whole columns or deals the
+    lists of a run of columns to the wavefronts of a workgroup, depending on how well whole columns fill the chip
+    (on 256 compute units: 8192 and 70 columns whole, 9000, 11008 and 33000 dealt, the last with more columns per
+    workgroup than it keeps sums for at a time).  PReLU and the bias go through the same epilogue in both."""
+    W, X, b = si.make_inputs(M, K, N, 0.5, "normal", seed=131 + M + N)
+    _, Xi, _ = si.make_inputs(M, K, N, 0.5, "int8", seed=132 + M + N)
+    W[:, 3] = 0          # an empty column
+    W[:, 4] = 1          # a column without a -1 list
+    ot = oracle.tcsc_build(W)
+    Yd, A, _ = oracle.tstgemm(X, ot, b)
+    Y, h = gpu_tstgemm(W, X, b)
+    assert_close(Y, Yd, A, f"{M}x{K}x{N}")
+    assert np.array_equal(gpu_tstgemm(W, Xi, b, handle=h)[0], oracle.tstgemm(Xi, ot, b)[0].astype(np.float32))
+    alpha = np.linspace(-0.5, 1.5, N).astype(np.float32)
+    Ya, _ = gpu_tstgemm(W, X, b, handle=h, alpha=alpha)
+    Yp, Ap = oracle.prelu(Yd, A, alpha)
+    assert_close(Ya, Yp, Ap, f"{M}x{K}x{N} PReLU")
