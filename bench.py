@@ -372,6 +372,12 @@ def main():
     roof["call_frac"] = roof["frac"] * kernel_ms / call_ms   # the same work over the time of the whole call
     if not decode:
         roof["alu_frac"] = roof["achieved"] / PEAK_ALU_ADD_TFLOPS
+        # What this build can reach at most: without packed fp32 a compute unit issues one vector instruction per
+        # clock (64 lanes), which is the same 39.3 T lane-operations/s as the LDS port's gathers, and every 16-byte
+        # gather costs four additions and one address instruction.  The counters say the gather kernels sit on this
+        # bound (0.99 vector instructions per clock and compute unit on C2, profiles/shader_counters_all_configs.md).
+        roof["valu_issue_bound"] = PEAK_LDS_GATHER_TFLOPS * 4.0 / 5.0
+        roof["frac_of_valu_issue_bound"] = roof["achieved"] / roof["valu_issue_bound"]
     if warm_ms is not None:
         roof["warm_cache_call_ms"] = warm_ms
         roof["warm_cache_note"] = ("one matrix called again and again: its index data comes from the 256 MB Infinity Cache, "
