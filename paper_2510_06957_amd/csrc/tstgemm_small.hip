@@ -203,23 +203,23 @@ __device__ __forceinline__ void run_slice(float4v &acc, const int4v &h, rsrc_t r
     }
     // Whole steps, two per turn.  In flight when a step is about to start: its own entries, those of the step behind
     // it if there is one, and `next` once the last step's entries have been requested: two younger requests when two
-    // steps are left, one otherwise.
-    while (left > 0) {
-        if (left == 2) read_step<SH, 2>(v, qa, base); else read_step<SH, 1>(v, qa, base);
+    // steps are left, one otherwise.  The wait is for "at most one younger" in every case: with two steps left it then
+    // also waits for the entries of the last step, requested a step ago, and the loop has one path instead of two.
+    for (; left > 0; left -= 2, at += 8 * CH) {   // (one exit: with a second one in the middle the compiler builds flags around it)
+        read_step<SH, 1>(v, qa, base);
         if (left > 2) {
             list_load(qa, r, lane16, at + 8 * CH);
             if (left == 3) next();
         }
         sums4();
-        if (--left == 0) break;
-        if (left == 2) read_step<SH, 2>(v, qb, base); else read_step<SH, 1>(v, qb, base);
-        if (left > 2) {
-            list_load(qb, r, lane16, at + 12 * CH);
-            if (left == 3) next();
+        if (left > 1) {
+            read_step<SH, 1>(v, qb, base);
+            if (left > 3) {
+                list_load(qb, r, lane16, at + 12 * CH);
+                if (left == 4) next();
+            }
+            sums4();
         }
-        sums4();
-        --left;
-        at += 8 * CH;
     }
 }
 
@@ -502,12 +502,13 @@ hipError_t launch_small(const float *X, const tcsc *t, const float *b, float *Y,
     if (k_slices == 0) k_slices = (short_k || groups >= slots) ? 1 : (int)((slots + groups - 1) / groups);
     // Which walk of the lists: by the mean length of a slice (the entries of one list inside one block of rows of W) in
     // steps of the wavefront (4 G entries).  Measured, time of the kernel with the requests placed by hand against the
-    // plain walk: 4 steps (M = 64 and M = 16 at 50 %) 6 % and 9 % faster; 2 steps (M = 64 and M = 32 at 25 %) 5 % and
-    // 1.5 % slower; 1 step and less (M = 64 at 12.5 % and 6.25 %) 19 % and 13 % slower.  From 3 steps on it is taken.
+    // plain walk: 4 steps (M = 64, 32 and 16 at 50 %) 10 %, 11 % and 9 % faster; 2 steps (M = 64, 32 and 16 at 25 %)
+    // 3 %, 5 % and 0 % faster; 1 step and less (M = 64 at 12.5 % and 6.25 %) 11 % and 13 % slower.  From 1.5 steps on
+    // it is taken.
     const int block_rows = STAGE / (4 * (256 / G));
     const long long n_blocks = (l.K + block_rows - 1) / block_rows;
     const bool long_slices = c.list_walk ? c.list_walk == 2
-                                         : (double)(l.nnz_pos + l.nnz_neg) >= 2.0 * (3.0 * 4 * G) * (double)n_blocks * (double)l.N;
+                                         : (double)(l.nnz_pos + l.nnz_neg) >= 2.0 * (1.5 * 4 * G) * (double)n_blocks * (double)l.N;
     const int shape = G * 8 + ncw;
 #define TST_SMALL(NCW_, G_) \
     case G_ * 8 + NCW_: \
