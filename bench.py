@@ -39,11 +39,11 @@ PEAK_ALU_INSTR_T = 256 * 64 * 2.4e9 / 1e12     # vector lane-instructions per se
 _T_ALL = "profiles/hbm_traffic_all_configs.md"
 _T_OTHER = "profiles/hbm_traffic_other_workloads.md"
 MEASURED_TRAFFIC = {
-    ("C1", "tcsc"): (1790176, _T_ALL), ("C2", "tcsc"): (46313921, _T_ALL), ("C3a", "tcsc"): (46358550, _T_ALL),
-    ("C3b", "tcsc"): (46380763, _T_ALL), ("C4-1", "tcsc"): (46061228, _T_ALL), ("C4-8", "tcsc"): (47343438, _T_ALL),
-    ("C5a", "tcsc"): (929248548, _T_ALL), ("C5b", "tcsc"): (922846304, _T_ALL), ("C5c", "tcsc"): (902670668, _T_ALL),
-    ("M64-K16384-N4096-d0.5", "tcsc"): (167681434, _T_OTHER),
-    ("C4-1", "packed"): (9611264, _T_OTHER), ("C4-8", "packed"): (11882291, _T_OTHER),
+    ("C1", "tcsc"): (1820253, _T_ALL), ("C2", "tcsc"): (46305018, _T_ALL), ("C3a", "tcsc"): (46361795, _T_ALL),
+    ("C3b", "tcsc"): (46404792, _T_ALL), ("C4-1", "tcsc"): (46039073, _T_ALL), ("C4-8", "tcsc"): (47360812, _T_ALL),
+    ("C5a", "tcsc"): (929168828, _T_ALL), ("C5b", "tcsc"): (922709707, _T_ALL), ("C5c", "tcsc"): (902583812, _T_ALL),
+    ("M64-K16384-N4096-d0.5", "tcsc"): (163358221, _T_OTHER),
+    ("C4-1", "packed"): (9610285, _T_OTHER), ("C4-8", "packed"): (11881214, _T_OTHER),
 }
 ORACLE_FLAGS = "gcc -O3 -fstrict-aliasing -DNDEBUG -fopenmp (the paper's flags, Sec. 4, without -march=native)"
 INFINITY_CACHE_BYTES = 256 << 20
