@@ -138,7 +138,8 @@ typedef struct tcsc_layout {
  * M <= 8 reads them, and every other form is derived from them on the GPU):
  */
 #define TCSC_FORM_ROWSETS 1u     /* masks: the large-M path of tstgemm(), M > 64 */
-#define TCSC_FORM_CUTS 2u        /* list_cuts: the small-tile path of tstgemm(), 8 < M <= 64 */
+#define TCSC_FORM_CUTS 2u        /* list_cuts: the small-tile path of tstgemm(), 8 < M <= 64 (a matrix with 2^30 or more
+                                    entries of one sign takes the large-M path for these M too: ROWSETS) */
 #define TCSC_FORM_LISTS16 4u     /* padded 16-bit lists (only where K <= 65535): M <= 8 reads half the bytes */
 #define TCSC_FORM_SIGNED 8u      /* signed_index: tstgemm_signed() */
 #define TCSC_FORM_PACKED 16u     /* packed: tstgemm_packed(); built from the row sets, so it selects ROWSETS too */
@@ -175,7 +176,8 @@ int tcsc_upload(tcsc_t *t, void *dev_buf, size_t bytes, void *stream);
  * M >= 1 arbitrary; K, N must equal the handle's.  M <= 8 takes the small-M kernel (X resident in the LDS, in
  * chunks of K if it is larger than 150 KiB; TCSC lists streamed -- their padded 16-bit copy where there is one
  * and X fits the LDS whole), 8 < M <= 64 the small-tile kernel (one tile of
- * X, lists read from the TCSC arrays between the list cuts), everything else the large-M path (row sets).
+ * X, lists read from the TCSC arrays between the list cuts; not for matrices with 2^30 or more entries of one sign,
+ * whose lists its 32-bit byte offsets do not reach), everything else the large-M path (row sets).
  * Asynchronous: the kernels are enqueued on `stream` (a hipStream_t, NULL = null stream), no host
  * synchronisation, no allocation.
  * Device data are not validated.  Errors: EINVAL, ENOTUPLOADED, ENOFORM, EWORKSPACE, EHIP (launch failure).

@@ -75,7 +75,7 @@ __device__ __forceinline__ rsrc_t list_rsrc(const int32_t *list)
     const uintptr_t p = reinterpret_cast<uintptr_t>(list);
     return rsrc_t{(int)(uint32_t)p, (int)(uint32_t)((p >> 32) & 0xffffu), 0x7fffffff, 0x00020000};
 }
-__device__ __forceinline__ void list_load(int4v &q, rsrc_t list, int lane_offset, int at)
+__device__ __forceinline__ void list_load(int4v &q, rsrc_t list, int lane_offset, unsigned at)   // at: byte offset, < 4 GiB
 {
     asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=&v"(q) : "v"(lane_offset), "s"(list), "s"(at) : "memory");
 }
@@ -95,7 +95,7 @@ template <int G> __device__ __forceinline__ void load_head(int4v &q, rsrc_t list
 {
     const int head = n & (Geo<G>::CH - 1);
     const int slots = head ? (head + G - 1) / G : 4;
-    list_load(q, list, __mul24(g, 4 * slots), 4 * first);
+    list_load(q, list, __mul24(g, 4 * slots), 4u * (unsigned)first);
 }
 
 // LDS reads as asm statements: nothing is scheduled between the instructions of one statement, and the waits are
@@ -163,7 +163,7 @@ __device__ __forceinline__ void run_slice(float4v &acc, const int4v &h, rsrc_t r
 {
     constexpr int CH = Geo<G>::CH, SH = Geo<G>::SH;
     const int head = n & (CH - 1);
-    int at = 4 * (first + head);   // byte offset of the first whole step
+    unsigned at = 4u * (unsigned)(first + head);   // byte offset of the first whole step (below 4 GiB)
     int left = (n - head) / CH;    // whole steps to go
     int4v qa, qb;                  // the entries of the two steps behind the one in hand
     asm volatile("" : "=v"(qa), "=v"(qb));   // (defined as far as the compiler is concerned: no code to initialise them)

@@ -207,6 +207,11 @@ def test_workspace_bytes():
     lo, hi = tg.tstgemm_workspace_bytes(4096, 8192, 8192)
     assert lo == 256 * 8192 * 4 and hi == 16 * lo                               # C5: 16 tiles, K not sliced
     assert tg.tstgemm_workspace_bytes(100, 70, 5)[0] == 128 * 128 * 4           # 128-row tile, K padded to 128
+    # a matrix that can hold 2^30 entries per sign may have to go through the large-M kernel for any M > 8 (the
+    # small-tile kernel addresses its lists with 32-bit byte offsets): the figures then cover both
+    lo, hi = tg.tstgemm_workspace_bytes(64, 65536, 65536)
+    lo_l, hi_l = tg.tstgemm_workspace_bytes(128, 65536, 65536)
+    assert lo == max(64 * 65536 * 4, lo_l) and hi >= hi_l
     lib = tg.binding._load()
     assert lib.tstgemm_workspace_bytes(0, 1, 1, None, None) == -1 and lib.tstgemm_workspace_bytes(1, 1, 1, None, None) == 0
 
