@@ -374,8 +374,8 @@ def main():
         roof["alu_frac"] = roof["achieved"] / PEAK_ALU_ADD_TFLOPS
         # What this build can reach at most: without packed fp32 a compute unit issues one vector instruction per
         # clock (64 lanes), which is the same 39.3 T lane-operations/s as the LDS port's gathers, and every 16-byte
-        # gather costs four additions and one address instruction.  The counters say the gather kernels sit on this
-        # bound (0.99 vector instructions per clock and compute unit on C2, profiles/shader_counters_all_configs.md).
+        # gather costs four additions and one address instruction.  C5a runs on this bound (0.80 of the LDS roofline),
+        # C2 at nine tenths of it (counters: profiles/shader_counters_all_configs.md).
         roof["valu_issue_bound"] = PEAK_LDS_GATHER_TFLOPS * 4.0 / 5.0
         roof["frac_of_valu_issue_bound"] = roof["achieved"] / roof["valu_issue_bound"]
     if warm_ms is not None:
