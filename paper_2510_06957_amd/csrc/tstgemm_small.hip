@@ -14,10 +14,14 @@
 //     falls into a block of rows of W (the paper's blocking, Sec. 3) is a slice of row_index_pos / _neg; the
 //     re-blocking pass stores where the slices start (list_cuts, a cut every 256 rows).  A lane loads 4 consecutive
 //     row numbers with one 16-byte load, 4 G per wavefront; a row number costs one VALU instruction (shift and add to
-//     the lane's LDS address) and no scalar work.  What the kernel waits for is these loads: a wavefront's loads
-//     return in order, and a step cannot start before its entries are there.  So the entries of a step are requested
-//     two steps ahead, the first entries of a slice a slice ahead and behind every other request of the slice
-//     before, and a step costs the vector ALU nothing but its four addresses and sixteen additions;
+//     the lane's LDS address) and no scalar work.  There are two walks of a slice.  The plain one (run_short_slice)
+//     takes a slice in steps of 4 G entries, the last one padded with the row of zeros, entries requested one step
+//     ahead: fewest instructions per slice, which is what counts where slices are a step or less.  The other one
+//     (run_slice), for longer slices: the vector ALU's issue slots are what the kernel fills, and behind them it
+//     waits for the loads of the entries -- a wavefront's loads return in order, and a step cannot start before its
+//     entries are there -- so a step costs the vector ALU nothing but its four addresses and sixteen additions, the
+//     partly filled step takes only the gathers it needs, the entries of a step are requested two steps ahead and
+//     the first entries of a slice two slices ahead, behind every other request of the slice that issues them;
 //   * the workgroup (16 wavefronts = 16 NCW columns) keeps one block of the packed X tile in the LDS (64 KiB:
 //     256 rows of W at TM = 64, 512 at TM = 32, 1024 at TM = 16; tile[k][TM]) with a row of zeros in front of it for the slots behind
 //     the end of a slice; two workgroups share a compute unit, one computes while the other exchanges its tile;
