@@ -98,6 +98,21 @@ def cpu_baseline(W, X, b, nnz, variant="tcsc", budget_s=10.0):
     return out
 
 
+def large_cols_per_wave(m_tiles, n_pad, density, cus):
+    """Columns of Y per wavefront the large-M path takes for a call in one slab: the library's rule, restated."""
+    if n_pad % 128:
+        return 4
+    gain8 = (3760.0 * density + 520.0) / (3966.0 * density + 316.0)
+    slots = 2 * cus
+    groups8 = m_tiles * (n_pad // 128)
+    rounds8, rounds4 = -(-groups8 // slots), -(-2 * groups8 // slots)
+    if groups8 >= slots and 2.0 * rounds8 <= rounds4 * gain8:
+        return 8
+    if groups8 < slots and 2 * groups8 >= slots and gain8 >= 1.3:
+        return 8
+    return 4
+
+
 def measured_peaks(tg, torch, stream, index_bytes):
     """What the machine delivers on the two resources the kernels are priced against, from the library's two probe
     kernels, run right after the timed work (clocks up): conflict-free 16-byte LDS reads at the large-M kernel's
@@ -134,9 +149,21 @@ def measured_peaks(tg, torch, stream, index_bytes):
         ms = best_ms(lambda: tg.tstgemm_probe_stream_read(small, stream))
         out["cached_stream_read_gb_per_s"] = small.numel() / (ms * 1e-3) / 1e9
         out["cached_stream_read_bytes"] = small.numel()
+    # the tile exchange of the tiled kernels by itself: 64 KiB pieces of a 4 MiB buffer (the size of C2's packed X: it
+    # stays in the L2s) into the LDS of 2 x 16 wavefronts per compute unit, between the same two barriers
+    tiles = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
+    tiles.zero_()
+    copied = [0]
+
+    def tile_copy():
+        copied[0] = tg.tstgemm_probe_tile_copy(tiles, 200, stream)
+    ms = best_ms(tile_copy)
+    out["tile_copy_tb_per_s"] = copied[0] / (ms * 1e-3) / 1e12
+    del tiles
     out["note"] = ("probe kernels of the library (tstgemm_probe_lds_read: 2 x 16 wavefronts per CU, ds_read_b128 only; "
-                   "tstgemm_probe_stream_read: 16-byte loads, grid-stride), best of 5, at the clock the chip holds under "
-                   "that load; the datasheet peaks assume 2.4 GHz and 8 TB/s")
+                   "tstgemm_probe_stream_read: 16-byte loads, grid-stride; tstgemm_probe_tile_copy: 64 KiB pieces of a 4 MiB "
+                   "buffer into the LDS, load - barrier - LDS write - barrier, 2 x 16 wavefronts per CU), best of 5, at the "
+                   "clock the chip holds under that load; the datasheet peaks assume 2.4 GHz and 8 TB/s")
     return out
 
 
@@ -378,6 +405,21 @@ def main():
         # C2 at nine tenths of it (counters: profiles/shader_counters_all_configs.md).
         roof["valu_issue_bound"] = PEAK_LDS_GATHER_TFLOPS * 4.0 / 5.0
         roof["frac_of_valu_issue_bound"] = roof["achieved"] / roof["valu_issue_bound"]
+    if not decode and not small:
+        # Bytes the main kernel copies from the packed X (in the L2s) into the LDS: every workgroup one K-block of its
+        # row tile (64 rows of W x TM rows of X x 4 bytes) per K-block it walks, whatever the density.  The columns
+        # per workgroup follow the library's own rule for its launch shape (tstgemm_large.hip, choose_shape), restated
+        # here; an override on the command line takes its place.
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        tm = 128 if wl.M <= 128 else 256
+        m_tiles = -(-wl.M // tm)
+        ncw = args.cols_per_wave or large_cols_per_wave(m_tiles, lay.n_pad, nnz / (wl.K * wl.N), cus)
+        if ncw == 8 and lay.n_pad % 128:
+            ncw = 4
+        tile_bytes = m_tiles * (lay.n_pad // (16 * ncw)) * lay.n_kblocks * 64 * tm * 4
+        roof["tile_copy"] = {"columns_per_workgroup": 16 * ncw, "bytes_per_launch": tile_bytes,
+                             "tb_per_s": tile_bytes / (kernel_ms * 1e-3) / 1e12,
+                             "note": "packed X from the L2s into the LDS, one K-block of a row tile per workgroup and K-block"}
     if warm_ms is not None:
         roof["warm_cache_call_ms"] = warm_ms
         roof["warm_cache_note"] = ("one matrix called again and again: its index data comes from the 256 MB Infinity Cache, "
@@ -385,6 +427,10 @@ def main():
     if not args.no_probes:
         pk = measured_peaks(tg, torch, stream, index_bytes)
         roof["peak_measured"] = pk
+        if "tile_copy" in roof:
+            # how much of what the copies alone can reach the kernel's copies take: at low density this, not the
+            # gathers, is what the main kernel is made of
+            roof["tile_copy"]["frac_of_measured_copy_rate"] = roof["tile_copy"]["tb_per_s"] / pk["tile_copy_tb_per_s"]
         if roof["bound"] == "lds":
             roof["frac_of_measured_peak"] = roof["achieved"] / pk["lds_gather_tadds_per_s"]
             roof["call_frac_of_measured_peak"] = roof["frac_of_measured_peak"] * kernel_ms / call_ms

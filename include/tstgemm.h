@@ -307,9 +307,9 @@ int tstgemm_signed(const float *X, const tcsc_t *t, const float *b, float *Y, in
 int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, int M, int K, int N, void *stream);
 
 /*
- * Measurement probes (not part of the product path): what the machine delivers on the two resources the
+ * Measurement probes (not part of the product path): what the machine delivers on the resources the
  * kernels are priced against (operational intensity and peak, Sec. 4), for a benchmark that wants the
- * measured rate beside the datasheet one.  Both only enqueue one kernel on `stream`; the caller times it.
+ * measured rate beside the datasheet one.  Each only enqueues one kernel on `stream`; the caller times it.
  *
  * tstgemm_probe_lds_read: 2 workgroups of 16 wavefronts per compute unit (the large-M kernel's occupancy), every
  * wavefront issues 8 * iters conflict-free 16-byte-per-lane LDS reads and nothing else.  *bytes_read (HOST,
@@ -318,9 +318,17 @@ int tstgemm_packed(const float *X, const tcsc_t *t, const float *b, float *Y, in
  * tstgemm_probe_stream_read: reads buf (DEVICE, 16-byte aligned, bytes >= 16; whole 16-byte pieces are read,
  * a tail of bytes % 16 is not) once with 16-byte loads, grid-stride, 8 workgroups of 256 threads per
  * compute unit.  Errors: EINVAL, EHIP.
+ *
+ * tstgemm_probe_tile_copy: the tile exchange of the tiled paths (the blocks of Sec. 3 "Blocking" on their way into
+ * the LDS) and nothing else: 2 workgroups of 16 wavefronts per compute unit, each copies `iters` times a 64 KiB
+ * piece of buf (DEVICE, 16-byte aligned, bytes >= 65536; the whole 64 KiB pieces of it, taken in turn, workgroup w
+ * starting at piece w) into its LDS -- 16-byte loads, barrier, 16-byte LDS writes, barrier.  With a buffer of a few
+ * MiB the pieces come from the L2s, as the packed copy of X does in a call.  *bytes_copied (HOST, may be NULL)
+ * receives the bytes all workgroups copy together.  1 <= iters <= 2^20.  Errors: EINVAL, EHIP.
  */
 int tstgemm_probe_lds_read(int iters, int64_t *bytes_read, void *stream);
 int tstgemm_probe_stream_read(const void *buf, size_t bytes, void *stream);
+int tstgemm_probe_tile_copy(const void *buf, size_t bytes, int iters, int64_t *bytes_copied, void *stream);
 
 /* Release the handle and its host arrays (not the device buffer).  NULL is allowed. */
 void tcsc_destroy(tcsc_t *t);

@@ -92,6 +92,8 @@ def _load():
     lib.tstgemm_probe_lds_read.restype = ci
     lib.tstgemm_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp]
     lib.tstgemm_probe_stream_read.restype = ci
+    lib.tstgemm_probe_tile_copy.argtypes = [vp, ctypes.c_size_t, ci, ctypes.POINTER(ctypes.c_int64), vp]
+    lib.tstgemm_probe_tile_copy.restype = ci
     for name in ("tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
                  "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tstgemm_signed", "tstgemm_packed",
                  "tcsc_signed_arrays", "tcsc_packed_codes", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms",
@@ -378,6 +380,16 @@ def tstgemm_probe_stream_read(buf, stream=None) -> int:
     nbytes = buf.numel() * buf.element_size()
     _check(_load().tstgemm_probe_stream_read(buf.data_ptr(), nbytes, _stream_ptr(stream)), "tstgemm_probe_stream_read")
     return nbytes // 16 * 16
+
+
+def tstgemm_probe_tile_copy(buf, iters: int, stream=None) -> int:
+    """Enqueue the tile-copy probe kernel over a CUDA tensor (at least 64 KiB); returns the bytes its workgroups copy
+    into their LDS together."""
+    n = ctypes.c_int64()
+    nbytes = buf.numel() * buf.element_size()
+    _check(_load().tstgemm_probe_tile_copy(buf.data_ptr(), nbytes, int(iters), ctypes.byref(n), _stream_ptr(stream)),
+           "tstgemm_probe_tile_copy")
+    return n.value
 
 
 def tcsc_destroy(t: Tcsc):

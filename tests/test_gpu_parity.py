@@ -321,6 +321,19 @@ def test_unaligned_operands(M, K, N):
     assert_close(Yd_.cpu().numpy(), Yd, A, f"unaligned {M}x{K}x{N}")
 
 
+def test_measurement_probes_run():
+    """The three probe kernels of the library run to completion and report the bytes they moved (what bench.py divides
+    by their time): LDS reads, a streaming read, and the tile exchange by itself on a buffer of one and of many pieces."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert tg.tstgemm_probe_lds_read(3) == 2 * cus * 1024 * 16 * 8 * 3
+    buf = torch.zeros((1 << 20) + 40, dtype=torch.uint8, device="cuda")
+    assert tg.tstgemm_probe_stream_read(buf[:1 << 20]) == 1 << 20
+    assert tg.tstgemm_probe_tile_copy(buf[:65536], 5) == 2 * cus * 65536 * 5
+    assert tg.tstgemm_probe_tile_copy(buf, 7) == 2 * cus * 65536 * 7          # 16 whole pieces; the 40 bytes behind them are not read
+    torch.cuda.synchronize()
+
+
 def test_profile_events_bracket_the_main_kernel():
     import torch
     W, X, b = si.make_workload("C1")

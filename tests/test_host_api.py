@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     assert {"tcsc_build", "tcsc_from_arrays", "tcsc_to_dense", "tcsc_dims", "tcsc_arrays", "tcsc_device_bytes",
             "tcsc_layout", "tcsc_upload", "tstgemm", "tstgemm_prelu", "tcsc_signed_arrays", "tcsc_packed_codes",
             "tstgemm_signed", "tstgemm_packed", "tstgemm_ex", "tstgemm_workspace_bytes", "tcsc_select_forms",
-            "tstgemm_probe_lds_read", "tstgemm_probe_stream_read", "tcsc_destroy",
+            "tstgemm_probe_lds_read", "tstgemm_probe_stream_read", "tstgemm_probe_tile_copy", "tcsc_destroy",
             "tcsc_strerror"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
@@ -170,6 +170,20 @@ def test_options_reject_bad_values():
     assert call(alpha=256, alpha_count=3) == -1 and call(alpha=256, alpha_count=8) == -3
     assert call(workspace=100, workspace_bytes=1 << 20) == -1                                      # not 256-byte aligned
     assert call(workspace=512, workspace_bytes=1 << 20) == -3
+
+
+def test_probes_reject_bad_arguments():
+    """The measurement probes check their arguments before they launch anything (no GPU needed for the refusals)."""
+    lib = tg.binding._load()
+    n = ctypes.c_int64(0)
+    fake = ctypes.c_void_p(256)
+    assert lib.tstgemm_probe_lds_read(0, ctypes.byref(n), None) == -1
+    assert lib.tstgemm_probe_stream_read(None, 1 << 20, None) == -1 and lib.tstgemm_probe_stream_read(fake, 8, None) == -1
+    assert lib.tstgemm_probe_tile_copy(None, 1 << 20, 1, ctypes.byref(n), None) == -1
+    assert lib.tstgemm_probe_tile_copy(fake, 65535, 1, ctypes.byref(n), None) == -1          # less than one 64 KiB piece
+    assert lib.tstgemm_probe_tile_copy(ctypes.c_void_p(260), 1 << 20, 1, ctypes.byref(n), None) == -1   # not 16-byte aligned
+    assert lib.tstgemm_probe_tile_copy(fake, 1 << 20, 0, ctypes.byref(n), None) == -1
+    assert n.value == 0
 
 
 def test_selected_forms_shrink_the_device_buffer():
